@@ -1,0 +1,215 @@
+/*
+ * fleet.h -- C ABI of the MI355X decode-step megakernel.
+ *
+ * One decode step of a Qwen3-style decoder stack (paper section 2.2: RMSNorm,
+ * QKV projection, attention over the KV cache, output projection, RMSNorm +
+ * gate/up projection, SiLU x multiply, down projection + residual; model shape
+ * of section 5.2) runs as ONE persistent HIP kernel that walks a static task
+ * graph (paper sections 3.1, 4.1, 4.2): wavefront-, CU-, chiplet- and
+ * device-scoped tasks, per-XCD task queues, event counters with two-level
+ * (XCD-local, then device) signalling.
+ *
+ * Conventions
+ *   - every function returns 0 (FLEET_OK) or a negative fleet_err code; nothing
+ *     throws or aborts.  fleet_strerror() names a code.
+ *   - "device" pointers are HIP device memory of the current device, "host"
+ *     pointers are ordinary host memory.  The library never takes ownership of
+ *     a caller buffer.
+ *   - bf16 tensors are raw 16-bit patterns; matrices are [out_features,
+ *     in_features] row-major, in_features contiguous (paper section 4.3: the
+ *     partition of chiplet k starts k*(N/8)*K elements after the base).
+ *   - one step in flight per fleet_t; calls on one fleet_t are not thread-safe.
+ */
+#ifndef FLEET_H
+#define FLEET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fleet fleet_t; /* opaque */
+
+enum fleet_err {
+  FLEET_OK = 0,
+  FLEET_EINVAL = -1,   /* bad shape, null pointer, batch out of range, ...      */
+  FLEET_ENOMEM = -2,   /* host or device allocation failed                       */
+  FLEET_EHIP = -3,     /* a HIP call failed; see fleet_last_status().hip_error   */
+  FLEET_ETIMEOUT = -4, /* a dependency wait ran out of time; the step aborted    */
+  FLEET_ESMALL = -5,   /* output buffer too small; *len holds the needed size    */
+  FLEET_EDEVICE = -6   /* the device cannot hold the persistent grid             */
+};
+
+/* Task scheduling (paper section 3.2 and Figure "tiling"). */
+enum fleet_sched {
+  FLEET_SCHED_COOPERATIVE = 0, /* N-split per XCD, M-major tile order inside (M-tile) */
+  FLEET_SCHED_UNAWARE = 1      /* 2-D tiles dealt to any worker, N-major               */
+};
+
+enum fleet_flags {
+  FLEET_FLAG_TRACE = 1,        /* record per-task tickets and timestamps               */
+  FLEET_FLAG_SINGLE_LEVEL = 2, /* every worker signals the device counter itself       */
+  FLEET_FLAG_CHAINED = 8       /* fleet_gemm: rep i+1 waits for rep i's event          */
+};
+
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn;
+  int32_t vocab;      /* 0: no final norm / LM head                                     */
+  int32_t max_batch;  /* 1..64                                                           */
+  int32_t max_seq;    /* KV slots per sequence; positions[b] < max_seq                   */
+  float rms_eps;      /* 1e-6                                                            */
+  float rope_theta;   /* 1e6                                                             */
+  int32_t sched_mode; /* enum fleet_sched                                                */
+  int32_t tile_m;     /* GEMM tile height along the batch for batch > 8: 16, 32, 64, or
+                         0 = whole batch rounded up to 16 (reads each weight once)       */
+  int32_t flags;      /* enum fleet_flags                                                */
+} fleet_shape_t;
+
+/* All device pointers, bf16, caller-owned, read-only, alive until fleet_destroy.
+ * The per-layer members are HOST arrays of n_layers device pointers. */
+typedef struct {
+  const void *embed;          /* [vocab, hidden] or NULL                                 */
+  const void *const *ln1;     /* [hidden]                                                */
+  const void *const *wqkv;    /* [(nq + 2 nkv) * head_dim, hidden], rows Q | K | V       */
+  const void *const *q_norm;  /* [head_dim]                                              */
+  const void *const *k_norm;  /* [head_dim]                                              */
+  const void *const *wo;      /* [hidden, nq * head_dim]                                 */
+  const void *const *ln2;     /* [hidden]                                                */
+  const void *const *wgu;     /* [2 * ffn, hidden], rows gate | up                       */
+  const void *const *wdown;   /* [hidden, ffn]                                           */
+  const void *final_norm;     /* [hidden] or NULL                                        */
+  const void *lm_head;        /* [vocab, hidden] or NULL                                 */
+} fleet_weights_t;
+
+typedef struct {
+  int32_t code;        /* FLEET_OK, FLEET_ETIMEOUT, ...                                  */
+  int32_t hip_error;   /* last hipError_t seen by the library                            */
+  int32_t task;        /* task whose wait timed out, or -1                               */
+  int32_t event;       /* event it waited for                                            */
+  int32_t observed;    /* counter value seen                                             */
+  int32_t needed;      /* counter value needed                                           */
+  int32_t n_xcd;       /* XCDs found on the device                                       */
+  int32_t workers[8];  /* workgroups that registered on each XCD in the last step        */
+} fleet_status_t;
+
+/*
+ * fleet_create: validate the shape, probe the device (CU count, XCD count),
+ * allocate descriptors, counters and scratch activations, build the RoPE table.
+ * Paper section 4.3 (task registration at model load).  *out is set on success.
+ * Requirements: head_dim == 128, hidden/ffn/(nq*head_dim) multiples of 16,
+ * n_q_heads a multiple of n_kv_heads with ratio <= 4, vocab a multiple of 16,
+ * hidden and ffn multiples of 32.
+ */
+int fleet_create(const fleet_shape_t *shape, const fleet_weights_t *weights, fleet_t **out);
+
+/*
+ * fleet_decode_step: one decode step for `batch` sequences, asynchronous on
+ * `stream` (a hipStream_t; NULL = the default stream).  Paper section 2.2 for
+ * what is computed, sections 4.1-4.2 for how it is executed.
+ *   hidden_in  device bf16 [batch, hidden], or NULL to gather embed[tokens[b]]
+ *   tokens     device int32 [batch] (used when hidden_in == NULL)
+ *   k_cache, v_cache  device bf16 [n_layers][max_batch][n_kv][max_seq][head_dim];
+ *              slot positions[b] of every layer is written, slots 0..positions[b]
+ *              are read
+ *   positions  device int32 [batch]: index of the new token (= valid slots before
+ *              the step); not advanced by the library
+ *   hidden_out device fp32 [batch, hidden]: residual stream after the last layer
+ *   logits     device fp32 [batch, vocab], or NULL
+ * The first call for a given batch size builds and uploads that batch's task
+ * graph (host work + one device allocation); later calls only launch.
+ * A dependency wait that times out aborts the step on the device; the next
+ * fleet_last_status() reports FLEET_ETIMEOUT.
+ */
+int fleet_decode_step(fleet_t *f, int32_t batch, const void *hidden_in, const int32_t *tokens,
+                      void *k_cache, void *v_cache, const int32_t *positions,
+                      float *hidden_out, float *logits, void *stream);
+
+/*
+ * fleet_decode_layers (test / measurement): layers [layer_begin, layer_end) on an
+ * fp32 residual stream.  x_in, x_out device fp32 [batch, hidden] (may alias);
+ * logits is written only when layer_end == n_layers and logits != NULL.  The
+ * other arguments are as in fleet_decode_step.  Same per-layer computation and
+ * the same task graph as the full step (paper section 2.2).
+ */
+int fleet_decode_layers(fleet_t *f, int32_t batch, int32_t layer_begin, int32_t layer_end,
+                        const float *x_in, void *k_cache, void *v_cache,
+                        const int32_t *positions, float *x_out, float *logits, void *stream);
+
+/* fleet_destroy: free everything the library allocated.  NULL is accepted. */
+int fleet_destroy(fleet_t *f);
+
+/*
+ * fleet_gemm (test / measurement): y = x . W^T as `reps` back-to-back device-tasks
+ * of the persistent kernel, the GEMM of paper section 3.2 in isolation.
+ *   x         device bf16 [B, K]
+ *   w_copies  HOST array of n_copies device pointers, each bf16 [N, K]; rep i
+ *             reads copy i % n_copies (rotating over more than the last-level
+ *             cache keeps the timing HBM-bound)
+ *   y         device fp32 [B, N]
+ *   sched_mode, tile_m  as in fleet_shape_t
+ *   elapsed_ms  HOST float or NULL: time of the one kernel launch that runs all
+ *             reps, measured with HIP events on `stream`
+ * K a multiple of 32, N of 16, 1 <= B <= 64.  Synchronous: returns after the
+ * kernel has finished (it allocates and frees its own descriptors).
+ */
+int fleet_gemm(int32_t B, int32_t K, int32_t N, const void *x, const void *const *w_copies,
+               int32_t n_copies, float *y, int32_t sched_mode, int32_t tile_m, int32_t flags,
+               int32_t reps, void *stream, float *elapsed_ms);
+
+/*
+ * fleet_graph_build (host only, no device needed): the task graph the library
+ * would run for `batch` on a device with n_xcd chiplets, as int32 words:
+ *   header[32], ops[n_ops][16], tasks[n_tasks][16], events[n_events][4],
+ *   queue offsets[n_xcd + 1], queue entries[n_qent][4], layer marks[n_xcd][n_layers + 3],
+ *   residual-ready events[n_layers + 1]
+ * (word meanings documented in csrc/graph.hpp).  buf may be NULL to query the size; *len is
+ * in/out in bytes.  Paper sections 3.1 (task scopes, events), 3.2 (partitioning,
+ * traversal order), 4.3 (per-chiplet partition pointers).
+ */
+int fleet_graph_build(const fleet_shape_t *shape, int32_t batch, int32_t n_xcd,
+                      int32_t n_workers, void *buf, size_t *len);
+
+/* fleet_graph_dump: the same words for the graph `f` runs at `batch`. */
+int fleet_graph_dump(fleet_t *f, int32_t batch, void *buf, size_t *len);
+
+/*
+ * fleet_trace_read (needs FLEET_FLAG_TRACE): copy the last step's execution
+ * records to host memory after synchronising the device.  Each record is 8
+ * int32 words: task, worker (workgroup id), xcd, tiles done, start ticket, end
+ * ticket, start time, end time (100 MHz ticks relative to the first record).
+ * Tickets come from one device-wide counter, so "end ticket of a predecessor <
+ * start ticket of a successor" checks the dependency order (paper section 3.1).
+ */
+int fleet_trace_read(fleet_t *f, void *buf, size_t *len);
+
+/* fleet_last_status: synchronise the device and report the last step's outcome. */
+int fleet_last_status(fleet_t *f, fleet_status_t *out);
+
+/*
+ * fleet_device_probe: XCD id (hardware XCC_ID) of each of n_blocks workgroups of
+ * a grid launched the way the persistent kernel is; xcd_of_block is a HOST array
+ * of n_blocks int32.  Paper section 4.1 (workers discover their XCD).
+ */
+int fleet_device_probe(int32_t n_blocks, int32_t *xcd_of_block);
+
+/*
+ * Traffic accounting, closed forms (paper section 5.4, Table "weight sizes",
+ * Eq. "l2-hit", Figure "roofline"): bytes are for bf16 weights.
+ */
+int64_t fleet_weight_bytes(int32_t K, int32_t N);                 /* K*N*2                */
+int64_t fleet_weight_bytes_per_xcd(int32_t K, int32_t N, int32_t n_xcd);
+int64_t fleet_l2_window_bytes(int32_t N, int32_t n_xcd, int32_t tile_n, int32_t tile_k);
+double fleet_l2_hit_model(int32_t batch, int32_t tile_m, int32_t workers_per_xcd);
+double fleet_effective_intensity(int32_t batch, double l2_hit);
+/* algorithmic HBM bytes of one decode step: every weight once + K,V of every
+ * attended slot + the new slot; positions is a HOST array of batch int32. */
+int64_t fleet_step_bytes(const fleet_shape_t *shape, int32_t batch, const int32_t *positions);
+
+const char *fleet_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEET_H */

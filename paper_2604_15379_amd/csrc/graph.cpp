@@ -1,0 +1,263 @@
+// Host-side task-graph builder (see graph.hpp for the layout and citations).
+#include "graph.hpp"
+
+#include <algorithm>
+#include <cstring>
+
+namespace fleetg {
+
+namespace {
+
+struct Builder {
+  Graph g;
+  int n_xcd, n_workers, sched, batch;
+  std::vector<std::vector<int32_t>> queues;  // per XCD, QENT_WORDS per entry
+  int stage = 0;
+
+  Builder(int nx, int nw, int sc, int b) : n_xcd(nx), n_workers(nw), sched(sc), batch(b), queues(nx) {}
+
+  int add_op(Body body, int layer, Epi epi, Path path, int K, int N, int unit_rows, int n_units,
+             int m_tiles, int tile_m, Buf in, Buf out, int aux, WKind wk) {
+    int32_t w[OP_WORDS] = {0};
+    w[O_BODY] = body; w[O_LAYER] = layer; w[O_EPI] = epi; w[O_PATH] = path; w[O_K] = K; w[O_N] = N;
+    w[O_UNIT_ROWS] = unit_rows; w[O_N_UNITS] = n_units; w[O_M_TILES] = m_tiles; w[O_TILE_M] = tile_m;
+    w[O_IN_BUF] = in; w[O_OUT_BUF] = out; w[O_AUX] = aux; w[O_WKIND] = wk; w[O_BATCH] = batch;
+    g.ops.insert(g.ops.end(), w, w + OP_WORDS);
+    return g.n_ops() - 1;
+  }
+  int add_event(int threshold, EventKind kind, int mask, int n_tasks) {
+    int32_t w[EVENT_WORDS] = {threshold, kind, mask, n_tasks};
+    g.events.insert(g.events.end(), w, w + EVENT_WORDS);
+    return g.n_events() - 1;
+  }
+  int add_task(int op, Scope scope, int xcd, int a0, int a1, int a2, int a3, int wait_ev, int sig_ev) {
+    int32_t w[TASK_WORDS] = {0};
+    w[T_OP] = op; w[T_SCOPE] = scope; w[T_XCD] = xcd; w[T_A0] = a0; w[T_A1] = a1; w[T_A2] = a2;
+    w[T_A3] = a3; w[T_WAIT_EVENT] = wait_ev; w[T_SIGNAL_EVENT] = sig_ev; w[T_STAGE] = stage;
+    g.tasks.insert(g.tasks.end(), w, w + TASK_WORDS);
+    return g.n_tasks() - 1;
+  }
+  void push_q(int xcd, int first, int count, Dist d) {
+    int32_t w[QENT_WORDS] = {first, count, d, stage};
+    queues[xcd].insert(queues[xcd].end(), w, w + QENT_WORDS);
+  }
+
+  // A stage of CU-tasks, one per item; item i belongs to XCD key(i) % n_xcd in
+  // the cooperative schedule (round-robin inside the XCD), to any worker in the
+  // chiplet-unaware one.  args(i) fills A0..A3.  Returns the signalled event.
+  template <class KeyF, class ArgF>
+  int cu_stage(int op, int n_items, int wait_ev, KeyF key, ArgF args) {
+    int ev = add_event(n_items, EV_DIRECT, 0, n_items);
+    if (sched == FLEET_SCHED_UNAWARE) {
+      int first = g.n_tasks();
+      for (int i = 0; i < n_items; ++i) {
+        int a[4]; args(i, a);
+        add_task(op, S_CU, -1, a[0], a[1], a[2], a[3], wait_ev, ev);
+      }
+      for (int x = 0; x < n_xcd; ++x) push_q(x, first, n_items, D_DEV_RR);
+    } else {
+      for (int x = 0; x < n_xcd; ++x) {
+        int first = g.n_tasks(), cnt = 0;
+        for (int i = 0; i < n_items; ++i) {
+          if (key(i) % n_xcd != x) continue;
+          int a[4]; args(i, a);
+          add_task(op, S_CU, x, a[0], a[1], a[2], a[3], wait_ev, ev);
+          ++cnt;
+        }
+        if (cnt) push_q(x, first, cnt, D_XCD_RR);
+      }
+    }
+    ++stage;
+    return ev;
+  }
+
+  // One GEMM device-task.  Cooperative: one chiplet-task per XCD over a contiguous
+  // slice of the output units (section 3.2, N-split).  Unaware: 2-D tiles
+  // (unit group x m-tile) in N-major order, dealt to any worker.
+  int gemm_stage(int op, int wait_ev) {
+    const int32_t* o = &g.ops[(size_t)op * OP_WORDS];
+    const int U = o[O_N_UNITS], mt = o[O_M_TILES];
+    int ev;
+    if (sched == FLEET_SCHED_UNAWARE) {
+      int cu_units = std::max(1, U / std::max(1, n_workers));
+      int ng = (U + cu_units - 1) / cu_units;
+      ev = add_event(ng * mt, EV_DIRECT, 0, ng * mt);
+      int first = g.n_tasks();
+      for (int m = 0; m < mt; ++m)
+        for (int gi = 0; gi < ng; ++gi) {
+          int u0 = gi * cu_units, cnt = std::min(cu_units, U - u0);
+          add_task(op, S_CU, -1, u0, cnt, m, 0, wait_ev, ev);
+        }
+      for (int x = 0; x < n_xcd; ++x) push_q(x, first, ng * mt, D_DEV_RR);
+    } else {
+      int mask = 0, nx = 0;
+      for (int x = 0; x < n_xcd; ++x) {
+        int u0 = (int)((int64_t)U * x / n_xcd), u1 = (int)((int64_t)U * (x + 1) / n_xcd);
+        if (u1 > u0) { mask |= 1 << x; ++nx; }
+      }
+      ev = add_event(nx, EV_TWO_LEVEL, mask, nx);
+      for (int x = 0; x < n_xcd; ++x) {
+        int u0 = (int)((int64_t)U * x / n_xcd), u1 = (int)((int64_t)U * (x + 1) / n_xcd);
+        if (u1 <= u0) continue;
+        int t = add_task(op, S_CHIPLET, x, u0, u1 - u0, 0, 0, wait_ev, ev);
+        push_q(x, t, 1, D_CHIPLET);
+      }
+    }
+    ++stage;
+    return ev;
+  }
+
+  void mark_all() {
+    for (int x = 0; x < n_xcd; ++x) g.marks.push_back((int32_t)queues[x].size() / QENT_WORDS);
+  }
+
+  Graph finish(int n_layers, int tile_m, int path, int n_splits, int m_tiles) {
+    g.qoff.assign(n_xcd + 1, 0);
+    for (int x = 0; x < n_xcd; ++x) {
+      g.qoff[x + 1] = g.qoff[x] + (int32_t)queues[x].size() / QENT_WORDS;
+      g.qents.insert(g.qents.end(), queues[x].begin(), queues[x].end());
+    }
+    // marks were pushed stage-major ([mark][xcd]); store them [xcd][mark]
+    int n_marks = n_xcd ? (int)g.marks.size() / n_xcd : 0;
+    std::vector<int32_t> m((size_t)n_xcd * n_marks);
+    for (int k = 0; k < n_marks; ++k)
+      for (int x = 0; x < n_xcd; ++x) m[(size_t)x * n_marks + k] = g.marks[(size_t)k * n_xcd + x];
+    g.marks.swap(m);
+    g.header.assign(HEADER_WORDS, 0);
+    int32_t* h = g.header.data();
+    h[H_MAGIC] = MAGIC; h[H_VERSION] = 1; h[H_N_OPS] = g.n_ops(); h[H_N_TASKS] = g.n_tasks();
+    h[H_N_EVENTS] = g.n_events(); h[H_N_XCD] = n_xcd; h[H_N_QENT] = g.n_qent(); h[H_N_LAYERS] = n_layers;
+    h[H_BATCH] = batch; h[H_SCHED] = sched; h[H_TILE_M] = tile_m; h[H_PATH] = path;
+    h[H_N_SPLITS] = n_splits; h[H_N_WORKERS] = n_workers; h[H_M_TILES] = m_tiles;
+    h[H_TOTAL_WORDS] = (int32_t)(HEADER_WORDS + g.ops.size() + g.tasks.size() + g.events.size() +
+                                 g.qoff.size() + g.qents.size() + g.marks.size() + g.xready.size());
+    return std::move(g);
+  }
+};
+
+}  // namespace
+
+std::vector<int32_t> Graph::serialize() const {
+  std::vector<int32_t> out;
+  out.reserve(header.size() + ops.size() + tasks.size() + events.size() + qoff.size() + qents.size() +
+              marks.size() + xready.size());
+  for (const auto* v : {&header, &ops, &tasks, &events, &qoff, &qents, &marks, &xready})
+    out.insert(out.end(), v->begin(), v->end());
+  return out;
+}
+
+int resolve_tile_m(int batch, int tile_m) {
+  if (batch <= 8) return batch;  // FMA GEMV path: one tile holds the whole batch
+  if (tile_m == 0) return ((batch + 15) / 16) * 16;
+  return tile_m;
+}
+
+int attention_splits(int batch, int n_kv_heads, int n_workers) {
+  int pairs = std::max(1, batch * n_kv_heads);
+  int s = 1;
+  while (s * 2 <= 32 && pairs * s * 2 <= n_workers) s *= 2;
+  return s;
+}
+
+int check_shape(const fleet_shape_t& s) {
+  if (s.n_layers < 1 || s.hidden < 32 || s.ffn < 32 || s.n_q_heads < 1 || s.n_kv_heads < 1) return FLEET_EINVAL;
+  if (s.head_dim != 128) return FLEET_EINVAL;
+  if (s.n_q_heads % s.n_kv_heads || s.n_q_heads / s.n_kv_heads > 4) return FLEET_EINVAL;
+  if (s.hidden % 32 || s.ffn % 32) return FLEET_EINVAL;
+  if (s.vocab < 0 || s.vocab % 16) return FLEET_EINVAL;
+  if (s.max_batch < 1 || s.max_batch > 64 || s.max_seq < 1) return FLEET_EINVAL;
+  if (s.sched_mode != FLEET_SCHED_COOPERATIVE && s.sched_mode != FLEET_SCHED_UNAWARE) return FLEET_EINVAL;
+  if (s.tile_m != 0 && s.tile_m != 16 && s.tile_m != 32 && s.tile_m != 64) return FLEET_EINVAL;
+  if (!(s.rms_eps >= 0.f) || !(s.rope_theta > 0.f)) return FLEET_EINVAL;
+  return FLEET_OK;
+}
+
+Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_workers) {
+  Builder b(n_xcd, n_workers, s.sched_mode, batch);
+  const int H = s.hidden, hd = s.head_dim, nq = s.n_q_heads, nkv = s.n_kv_heads, F = s.ffn;
+  const int QD = nq * hd, NQKV = (nq + 2 * nkv) * hd;
+  const Path path = batch <= 8 ? P_FMA : P_MFMA;
+  const int ur = path == P_FMA ? 8 : 16;
+  const int tm = resolve_tile_m(batch, s.tile_m);
+  const int mt = (batch + tm - 1) / tm;
+  const int S = attention_splits(batch, nkv, n_workers);
+
+  auto row_key = [](int i) { return i; };
+  auto row_arg = [](int i, int* a) { a[0] = i; a[1] = a[2] = a[3] = 0; };
+
+  // stage: ingest (bf16 hidden or embedding gather -> fp32 residual stream)
+  b.mark_all();
+  int op_in = b.add_op(B_INGEST, -1, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_HIDDEN_IN, BUF_X, 0, W_EMBED);
+  int ev = b.cu_stage(op_in, batch, -1, row_key, row_arg);
+  b.g.xready.push_back(ev);
+
+  for (int l = 0; l < s.n_layers; ++l) {
+    b.mark_all();
+    int op_n1 = b.add_op(B_RMSNORM, l, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N, 0, W_LN1);
+    ev = b.cu_stage(op_n1, batch, ev, row_key, row_arg);
+
+    int op_qkv = b.add_op(B_GEMM, l, E_STORE_F32, path, H, NQKV, ur, NQKV / ur, mt, tm, BUF_N, BUF_QKV, 0, W_QKV);
+    ev = b.gemm_stage(op_qkv, ev);
+
+    int op_att = b.add_op(B_ATTN, l, E_STORE_F32, P_FMA, hd, QD, 0, 0, 1, batch, BUF_QKV,
+                          S > 1 ? BUF_PART : BUF_ATT, S, W_NONE);
+    ev = b.cu_stage(op_att, batch * nkv * S, ev,
+                    [S](int i) { return i / S; },
+                    [S, nkv](int i, int* a) { int p = i / S; a[0] = p / nkv; a[1] = p % nkv; a[2] = i % S; a[3] = S; });
+    if (S > 1) {
+      int op_mg = b.add_op(B_MERGE, l, E_STORE_F32, P_FMA, hd, QD, 0, 0, 1, batch, BUF_PART, BUF_ATT, S, W_NONE);
+      ev = b.cu_stage(op_mg, batch * nkv, ev, row_key,
+                      [S, nkv](int i, int* a) { a[0] = i / nkv; a[1] = i % nkv; a[2] = 0; a[3] = S; });
+    }
+    int op_o = b.add_op(B_GEMM, l, E_RESID_F32, path, QD, H, ur, H / ur, mt, tm, BUF_ATT, BUF_X, 0, W_O);
+    ev = b.gemm_stage(op_o, ev);
+
+    int op_n2 = b.add_op(B_RMSNORM, l, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N, 0, W_LN2);
+    ev = b.cu_stage(op_n2, batch, ev, row_key, row_arg);
+
+    // gate | up rows of one concatenated matrix; a unit is ur gate rows plus the
+    // matching ur up rows (aux = row offset of the up half), SwiGLU in the epilogue
+    int op_gu = b.add_op(B_GEMM, l, E_SWIGLU_BF16, path, H, F, ur, F / ur, mt, tm, BUF_N, BUF_H, F, W_GU);
+    ev = b.gemm_stage(op_gu, ev);
+
+    int op_dn = b.add_op(B_GEMM, l, E_RESID_F32, path, F, H, ur, H / ur, mt, tm, BUF_H, BUF_X, 0, W_DOWN);
+    ev = b.gemm_stage(op_dn, ev);
+    b.g.xready.push_back(ev);
+  }
+
+  // final stage: residual stream -> hidden_out, final norm -> BUF_N, then the LM head
+  b.mark_all();
+  int op_fin = b.add_op(B_FINAL, -1, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N,
+                        s.vocab > 0 ? 1 : 0, W_FINAL);
+  ev = b.cu_stage(op_fin, batch, ev, row_key, row_arg);
+  if (s.vocab > 0) {
+    int op_lm = b.add_op(B_GEMM, -1, E_STORE_F32, path, H, s.vocab, ur, s.vocab / ur, mt, tm, BUF_N,
+                         BUF_LOGITS, 0, W_LM);
+    ev = b.gemm_stage(op_lm, ev);
+  }
+  b.mark_all();
+  return b.finish(s.n_layers, tm, path, S, mt);
+}
+
+Graph build_gemm_graph(int B, int K, int N, int sched_mode, int tile_m, int flags, int reps,
+                       int n_copies, int n_xcd, int n_workers) {
+  Builder b(n_xcd, n_workers, sched_mode, B);
+  const Path path = B <= 8 ? P_FMA : P_MFMA;
+  const int ur = path == P_FMA ? 8 : 16;
+  const int tm = resolve_tile_m(B, tile_m);
+  const int mt = (B + tm - 1) / tm;
+  int ev = -1;
+  b.mark_all();
+  b.mark_all();
+  for (int r = 0; r < reps; ++r) {
+    int op = b.add_op(B_GEMM, r % std::max(1, n_copies), E_STORE_F32, path, K, N, ur, N / ur, mt, tm,
+                      BUF_GEMM_X, BUF_GEMM_Y, 0, W_GEMM_COPY);
+    int e = b.gemm_stage(op, (flags & 8) ? ev : -1);
+    ev = e;
+  }
+  b.mark_all();
+  b.g.xready.push_back(-1);
+  return b.finish(0, tm, path, 1, mt);
+}
+
+}  // namespace fleetg

@@ -1,0 +1,96 @@
+// Host-side task-graph builder for the decode-step megakernel.
+//
+// The graph follows the task model of paper section 3.1: every operator of a
+// layer (section 2.2) becomes one device-task, made of chiplet-tasks (GEMMs in
+// the cooperative schedule, one per XCD, section 3.2) or of CU-tasks (norms,
+// attention, and every GEMM tile of the chiplet-unaware schedule).  Tasks name
+// the event they wait for and the event they signal.  Everything is plain
+// int32 words so that the graph can be dumped, compared and uploaded as is.
+//
+// Serialized layout (int32 words, in this order):
+//   header [HEADER_WORDS]
+//   ops    [n_ops   ][OP_WORDS]
+//   tasks  [n_tasks ][TASK_WORDS]
+//   events [n_events][EVENT_WORDS]
+//   qoff   [n_xcd + 1]                  first queue entry of each XCD's queue
+//   qents  [n_qent  ][QENT_WORDS]       the per-XCD queues, concatenated
+//   marks  [n_xcd][n_layers + 3]        queue index (within the XCD's queue) of:
+//                                       ingest, layer 0..L-1, final stage, end
+//   xready [n_layers + 1]               event after which the residual stream
+//                                       entering layer l is complete
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "../../include/fleet.h"
+
+namespace fleetg {
+
+constexpr int HEADER_WORDS = 32, OP_WORDS = 16, TASK_WORDS = 16, EVENT_WORDS = 4, QENT_WORDS = 4;
+constexpr int32_t MAGIC = 0x464c5447;  // "FLTG"
+
+// header word indices
+enum {
+  H_MAGIC = 0, H_VERSION, H_N_OPS, H_N_TASKS, H_N_EVENTS, H_N_XCD, H_N_QENT, H_N_LAYERS,
+  H_BATCH, H_SCHED, H_TILE_M, H_PATH, H_N_SPLITS, H_N_WORKERS, H_M_TILES, H_TOTAL_WORDS
+};
+
+enum Body { B_INGEST = 0, B_RMSNORM = 1, B_GEMM = 2, B_ATTN = 3, B_MERGE = 4, B_FINAL = 5 };
+enum Epi { E_STORE_F32 = 0, E_RESID_F32 = 1, E_SWIGLU_BF16 = 2 };
+enum Path { P_FMA = 0, P_MFMA = 1 };
+enum Scope { S_WAVE = 0, S_CU = 1, S_CHIPLET = 2 };
+enum Dist { D_CHIPLET = 0, D_XCD_RR = 1, D_DEV_RR = 2 };
+enum EventKind { EV_DIRECT = 0, EV_TWO_LEVEL = 1 };
+
+// activation / caller buffers, resolved to pointers per step
+enum Buf {
+  BUF_NONE = 0, BUF_X, BUF_N, BUF_QKV, BUF_ATT, BUF_H, BUF_PART, BUF_HIDDEN_IN, BUF_TOKENS,
+  BUF_KC, BUF_VC, BUF_POS, BUF_HIDDEN_OUT, BUF_LOGITS, BUF_GEMM_X, BUF_GEMM_Y, N_BUF
+};
+
+// which caller weight an op reads (resolved with the op's layer)
+enum WKind {
+  W_NONE = 0, W_QKV, W_O, W_GU, W_DOWN, W_LM, W_LN1, W_LN2, W_FINAL, W_EMBED, W_GEMM_COPY
+};
+
+// op word indices
+enum {
+  O_BODY = 0, O_LAYER, O_EPI, O_PATH, O_K, O_N, O_UNIT_ROWS, O_N_UNITS, O_M_TILES, O_TILE_M,
+  O_IN_BUF, O_OUT_BUF, O_AUX, O_WKIND, O_BATCH, O_RESERVED
+};
+// task word indices.  A0..A3 by body:
+//   GEMM chiplet-task : A0 first unit, A1 unit count            (tiles = units x m_tiles)
+//   GEMM CU-task      : A0 first unit, A1 unit count, A2 m-tile
+//   ATTN              : A0 batch row, A1 kv head, A2 split, A3 n_splits
+//   MERGE             : A0 batch row, A1 kv head, A3 n_splits
+//   INGEST/RMSNORM/FINAL : A0 batch row
+enum { T_OP = 0, T_SCOPE, T_XCD, T_A0, T_A1, T_A2, T_A3, T_WAIT_EVENT, T_SIGNAL_EVENT, T_STAGE };
+// event word indices: threshold counts device-level signals (XCDs for a
+// two-level event, tasks for a direct one)
+enum { E_THRESHOLD = 0, E_KIND, E_XCD_MASK, E_N_TASKS };
+// queue entry word indices
+enum { Q_FIRST = 0, Q_COUNT, Q_DIST, Q_STAGE };
+
+struct Graph {
+  std::vector<int32_t> header, ops, tasks, events, qoff, qents, marks, xready;
+  int n_ops() const { return (int)ops.size() / OP_WORDS; }
+  int n_tasks() const { return (int)tasks.size() / TASK_WORDS; }
+  int n_events() const { return (int)events.size() / EVENT_WORDS; }
+  int n_qent() const { return (int)qents.size() / QENT_WORDS; }
+  std::vector<int32_t> serialize() const;
+};
+
+// tile_m actually used for `batch` (0 = whole batch rounded up to 16; FMA path: batch)
+int resolve_tile_m(int batch, int tile_m);
+// KV splits per (sequence, kv head)
+int attention_splits(int batch, int n_kv_heads, int n_workers);
+// validate a shape; returns FLEET_OK or FLEET_EINVAL
+int check_shape(const fleet_shape_t& s);
+
+// the decode-step graph for `batch` sequences on n_xcd chiplets, n_workers workgroups
+Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_workers);
+// `reps` GEMM device-tasks y = x W^T (rep i reads weight copy i % n_copies)
+Graph build_gemm_graph(int B, int K, int N, int sched_mode, int tile_m, int flags, int reps,
+                       int n_copies, int n_xcd, int n_workers);
+
+}  // namespace fleetg

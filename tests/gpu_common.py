@@ -1,0 +1,90 @@
+"""Helpers shared by the GPU parity tests: build a seeded model on the GPU, run the
+HIP path through the C ABI, run the CPU oracle on host copies of the same data."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2604_15379_amd as F
+import synth_inputs as si
+
+TOL = 2e-2   # max |err| <= TOL * RMS(reference): the bar stated for hidden states and logits
+
+
+def rms(a):
+    return float(np.sqrt(np.mean(np.asarray(a, np.float64) ** 2)))
+
+
+def assert_close(got, ref, what, tol=TOL):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    assert np.isfinite(got).all(), f"{what}: non-finite values"
+    err = float(np.abs(got - ref).max()) if got.size else 0.0
+    bound = tol * rms(ref)
+    assert err <= bound, f"{what}: max|err| {err:.4e} > {tol} * RMS = {bound:.4e}"
+    return err / max(rms(ref), 1e-30)
+
+
+class Model:
+    """Seeded weights / inputs on the GPU plus host views for the oracle."""
+
+    def __init__(self, shape: si.Shape, seed: int, batch: int, positions, with_embed=False):
+        self.shape, self.batch = shape, batch
+        g = si.Gen(seed, "cuda")
+        self.w = si.make_weights(shape, g, with_embed=with_embed)
+        self.hidden = si.make_hidden(shape, batch, g)
+        self.kc, self.vc = si.make_kv_cache(shape, g)
+        self.pos_host = np.ascontiguousarray(positions, np.int32)
+        assert self.pos_host.shape == (batch,)
+        self.pos = torch.tensor(self.pos_host, device="cuda")
+        self.w_host = si.weights_to_host(self.w)
+        self.hidden_host = si.to_host_u16(self.hidden)
+
+    def host_caches(self):
+        return si.to_host_u16(self.kc).copy(), si.to_host_u16(self.vc).copy()
+
+    def run_oracle(self, tokens=None, want_trace=False, flags=0):
+        k, v = self.host_caches()
+        out = oracle.decode_step(self.shape.asdict(), self.w_host, self.batch, self.pos_host, k, v,
+                                 hidden_in=None if tokens is not None else self.hidden_host,
+                                 tokens=tokens, want_trace=want_trace, flags=flags)
+        return out, k, v
+
+    def run_gpu(self, sched_mode=0, tile_m=0, flags=0, tokens=None, fleet=None):
+        """Returns (hidden_out, logits, k_cache, v_cache) as host arrays, plus the status."""
+        sh = self.shape
+        kc, vc = self.kc.clone(), self.vc.clone()
+        hout = torch.full((self.batch, sh.hidden), float("nan"), device="cuda", dtype=torch.float32)
+        logits = torch.full((self.batch, max(sh.vocab, 1)), float("nan"), device="cuda",
+                            dtype=torch.float32) if sh.vocab > 0 else None
+        own = fleet is None
+        f = fleet or F.fleet_create(sh.asdict(), self.w, sched_mode, tile_m, flags)
+        try:
+            tok = None if tokens is None else torch.tensor(tokens, device="cuda", dtype=torch.int32)
+            F.fleet_decode_step(f, self.batch, None if tok is not None else self.hidden, tok, kc, vc,
+                                self.pos, hout, logits, torch.cuda.current_stream().cuda_stream)
+            st = F.fleet_last_status(f)
+            assert st["code"] == 0, st
+            trace = F.fleet_trace_read(f) if flags & F.FLAG_TRACE else None
+            graph = F.parse_graph(F.fleet_graph_dump(f, self.batch)) if flags & F.FLAG_TRACE else None
+        finally:
+            if own:
+                F.fleet_destroy(f)
+        return (hout.cpu().numpy(), None if logits is None else logits.cpu().numpy(),
+                si.to_host_u16(kc), si.to_host_u16(vc), st, trace, graph)
+
+
+def check_new_kv(model: Model, k_gpu, v_gpu, k_ref, v_ref):
+    """The step writes only slot positions[b]; the values match the oracle's bf16 k, v
+    up to one bf16 rounding step (fp32 summation order may move a value across a tie)."""
+    k0, v0 = model.host_caches()
+    changed = np.zeros(k_ref.shape[:4], bool)
+    for b in range(model.batch):
+        changed[:, b, :, model.pos_host[b]] = True
+    assert np.array_equal(k_gpu[~changed], k0[~changed]), "K cache touched outside the new slot"
+    assert np.array_equal(v_gpu[~changed], v0[~changed]), "V cache touched outside the new slot"
+    for got, ref, nm in ((k_gpu, k_ref, "k"), (v_gpu, v_ref, "v")):
+        g = si.bf16_bits_to_f32(got[changed]).astype(np.float64)
+        r = si.bf16_bits_to_f32(ref[changed]).astype(np.float64)
+        ulp = np.maximum(np.abs(r), 1e-3) * 2.0 ** -7
+        assert np.all(np.abs(g - r) <= ulp), f"new {nm} entries differ by more than one bf16 step"
+        assert np.mean(got[changed] == ref[changed]) > 0.97, f"too many new {nm} entries differ"

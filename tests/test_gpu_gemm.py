@@ -1,0 +1,67 @@
+"""GPU parity of the GEMM device-task (the persistent kernel running only GEMM tasks)
+against the oracle's plain linear, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_15379_amd as F
+import synth_inputs as si
+from gpu_common import assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(B, K, N, sched=0, tile_m=0, flags=0, reps=1, n_copies=1, seed=1):
+    g = si.Gen(seed, "cuda")
+    x = g.normal_bf16((B, K), 1.0)
+    ws = [g.normal_bf16((N, K), 0.02) for _ in range(n_copies)]
+    y = torch.full((B, N), float("nan"), device="cuda", dtype=torch.float32)
+    ms = F.fleet_gemm(B, K, N, x, ws, y, sched, tile_m, flags, reps)
+    last = ws[(reps - 1) % n_copies]
+    ref = oracle.linear(si.bf16_bits_to_f32(si.to_host_u16(x)), si.to_host_u16(last))
+    return y.cpu().numpy(), ref, ms
+
+
+def test_device_probe_reports_every_xcd():
+    xcd = F.fleet_device_probe(256)
+    print("workgroups per XCD:", np.bincount(xcd, minlength=8).tolist(), "first 16:", xcd[:16].tolist(),
+          flush=True)
+    assert xcd.min() >= 0 and xcd.max() < 8
+    assert (np.bincount(xcd, minlength=xcd.max() + 1) > 0).all()
+
+
+# small shapes: several units per worker, ragged unit counts, K not a multiple of 512
+@pytest.mark.parametrize("B", [1, 2, 3, 5, 8, 9, 16, 20, 33, 64])
+@pytest.mark.parametrize("K,N", [(1024, 1536), (3072, 1024), (416, 272)])
+def test_gemm_small_shapes(B, K, N):
+    print(f"gemm B={B} K={K} N={N}", flush=True)
+    y, ref, _ = _run(B, K, N)
+    assert_close(y, ref, f"gemm B={B} K={K} N={N}", tol=1e-3)
+
+
+@pytest.mark.parametrize("sched,tile_m,flags", [(0, 16, 0), (1, 16, 0), (1, 0, 0), (0, 32, 0),
+                                                 (0, 16, F.FLAG_SINGLE_LEVEL), (0, 0, F.FLAG_CHAINED)])
+@pytest.mark.parametrize("B", [4, 48])
+def test_gemm_schedules_and_tiles(B, sched, tile_m, flags):
+    print(f"gemm modes B={B} sched={sched} tile_m={tile_m} flags={flags}", flush=True)
+    y, ref, _ = _run(B, 1024, 2048, sched, tile_m, flags, reps=3, n_copies=2)
+    assert_close(y, ref, "gemm", tol=1e-3)
+
+
+def test_cooperative_and_unaware_give_identical_bits():
+    # the same tiles with the same in-tile reduction order, mapped to workers two ways
+    for B in (1, 8, 32, 64):
+        a, _, _ = _run(B, 2048, 1024, 0, 16)
+        b, _, _ = _run(B, 2048, 1024, 1, 16)
+        assert np.array_equal(a, b), f"B={B}"
+
+
+# the Qwen3-8B GEMM shapes of the sweep
+@pytest.mark.parametrize("K,N", [(4096, 6144), (4096, 4096), (4096, 24576), (12288, 4096)])
+@pytest.mark.parametrize("B", [1, 8, 32, 64])
+def test_gemm_qwen3_shapes(B, K, N):
+    print(f"gemm qwen3 B={B} K={K} N={N}", flush=True)
+    y, ref, ms = _run(B, K, N)
+    print(f"  {ms * 1e3:.1f} us", flush=True)
+    assert_close(y, ref, f"gemm B={B} K={K} N={N}", tol=1e-3)
