@@ -1,0 +1,148 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-step megakernel on one MI355X.
+
+A "step" is one pass of the whole hot path: one decode step of the 36-layer
+Qwen3-8B-shaped stack (ingest, per layer RMSNorm / QKV / attention / O / RMSNorm /
+gate-up + SwiGLU / down, final norm, LM head) as one launch of the persistent kernel,
+on seeded synthetic weights and KV cache already resident in HBM.
+
+Prints ONE JSON line: decode-step latency in microseconds (lower is better), with a
+`roofline` object (algorithmic HBM bytes of one step / measured kernel time, against
+8 TB/s) and a `cpu_baseline` object (the CPU oracle timed on a bounded sample).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--kv", type=int, default=1024, help="valid KV slots per sequence before the step")
+    ap.add_argument("--kv-min", type=int, default=0, help="if > 0, per-sequence lengths uniform in [kv-min, kv]")
+    ap.add_argument("--layers", type=int, default=36)
+    ap.add_argument("--sched", type=int, default=0, help="0 cooperative (XCD), 1 chiplet-unaware")
+    ap.add_argument("--tile-m", type=int, default=0)
+    ap.add_argument("--flags", type=int, default=0)
+    ap.add_argument("--seed", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per step from rocprofv3 counters (reported as roofline.traffic)")
+    return ap.parse_args()
+
+
+def cpu_baseline(shape, w_dev, hidden_dev, batch, kv, seed):
+    """Time the CPU oracle on a bounded sample of the same workload: the first
+    `n_sample` layers plus the LM head, one sequence; report the full-step time
+    obtained by scaling the per-layer part to all layers."""
+    import numpy as np
+    import oracle
+    import synth_inputs as si
+    n_sample = min(4, shape.n_layers)
+    sh = si.Shape(**{**shape.asdict(), "n_layers": n_sample, "max_batch": 1, "max_seq": kv + 1})
+    wh = {k: [si.to_host_u16(a) for a in w_dev[k][:n_sample]] for k in si.PER_LAYER}
+    wh["final_norm"] = si.to_host_u16(w_dev["final_norm"])
+    wh["lm_head"] = si.to_host_u16(w_dev["lm_head"])
+    g = si.Gen(seed + 1000)
+    kc, vc = si.make_kv_cache(sh, g)
+    kc, vc = si.to_host_u16(kc), si.to_host_u16(vc)
+    hid = si.to_host_u16(hidden_dev[:1])
+    pos = np.array([kv], np.int32)
+    x0 = si.bf16_bits_to_f32(hid)
+    t0 = time.perf_counter()
+    x1, _ = oracle.decode_layers(sh.asdict(), wh, 1, 0, n_sample, x0, pos, kc, vc)
+    t_layers = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    n = oracle.rmsnorm(x1, wh["final_norm"], sh.rms_eps)
+    oracle.linear(n, wh["lm_head"])
+    t_head = time.perf_counter() - t0
+    full = (t_layers / n_sample * shape.n_layers + t_head) * batch
+    return {"value": full * 1e6, "unit": "us", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{n_sample} of {shape.n_layers} layers + LM head, 1 of {batch} sequences, KV {kv}: "
+                      f"{t_layers:.3f} s + {t_head:.3f} s, scaled to all layers and sequences"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: the decode step runs on a single MI355X and nothing in this "
+              "build shards across GPUs; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2604_15379_amd as F
+    import synth_inputs as si
+
+    torch.cuda.set_device(0)
+    B = a.batch
+    shape = si.qwen3_8b_shape(max_batch=B, max_seq=a.kv + 1, n_layers=a.layers)
+    g = si.Gen(a.seed, "cuda")
+    w = si.make_weights(shape, g)
+    hidden = si.make_hidden(shape, B, g)
+    kc, vc = si.make_kv_cache(shape, g)
+    if a.kv_min > 0:
+        pos_host = g.randint(a.kv_min, a.kv, B).cpu().numpy().astype(np.int32)
+    else:
+        pos_host = np.full(B, a.kv, np.int32)
+    pos = torch.tensor(pos_host, device="cuda")
+    hout = torch.empty((B, shape.hidden), device="cuda", dtype=torch.float32)
+    logits = torch.empty((B, shape.vocab), device="cuda", dtype=torch.float32)
+    f = F.fleet_create(shape.asdict(), w, a.sched, a.tile_m, a.flags)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        F.fleet_decode_step(f, B, hidden, None, kc, vc, pos, hout, logits, stream)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    st = F.fleet_last_status(f)
+    if st["code"] != 0:
+        raise SystemExit(f"decode step failed: {st}")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(a.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / a.steps
+    st = F.fleet_last_status(f)
+    if st["code"] != 0 or not torch.isfinite(logits).all():
+        raise SystemExit(f"decode step failed: {st}")
+
+    step_bytes = F.fleet_step_bytes(shape.asdict(), B, pos_host)
+    gbps = step_bytes / (ms * 1e-3) / 1e9
+    out = {
+        "metric": "decode_step_latency_us", "value": ms * 1e3, "unit": "us", "n_gpus": 1,
+        "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"Qwen3-8B-shaped decode step, {a.layers} layers + LM head, batch {B}, "
+                               f"KV {a.kv_min or a.kv}..{a.kv} per sequence, random bf16 weights (seed {a.seed})",
+                   "batch": B, "kv_len": a.kv, "sched_mode": ["cooperative", "unaware"][a.sched],
+                   "tile_m": a.tile_m, "flags": a.flags, "tokens_per_s": B / (ms * 1e-3)},
+        "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": gbps / HBM_PEAK_GBPS, "traffic": a.traffic_bytes,
+                     "algorithmic_bytes": step_bytes,
+                     "kernel": "fleet_persistent_kernel (one launch per step)"},
+        "l2_hit_model": F.fleet_l2_hit_model(B, a.tile_m or 16 * ((B + 15) // 16) if B > 8 else B or 1, 32),
+        "workers_per_xcd": st["workers"],
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, w, hidden, B, a.kv, a.seed)
+    F.fleet_destroy(f)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,283 @@
+"""CPU-side checks: the C-ABI library loads and exports what include/fleet.h declares,
+the accounting closed forms reproduce the paper's printed tables, and the host task-graph
+builder equals an independent re-derivation written here (plain integers, bit-exact)."""
+import json
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2604_15379_amd as F
+import synth_inputs as si
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLD = json.load(open(os.path.join(ROOT, "tests", "golden", "paper_tables.json")))
+
+
+# ------------------------------------------------------------------ ABI
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "fleet.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(fleet_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(F.EXPORTS), declared ^ set(F.EXPORTS)
+    lib = F.load_library()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert F.fleet_strerror(0) == "ok" and "timed out" in F.fleet_strerror(-4)
+
+
+def test_graph_build_rejects_bad_shapes():
+    sh = si.reduced_shape().asdict()
+    for bad in ({"head_dim": 64}, {"hidden": 1000}, {"n_q_heads": 7}, {"max_batch": 65},
+                {"vocab": 1001}, {"n_layers": 0}):
+        with pytest.raises(F.FleetError):
+            F.fleet_graph_build({**sh, **bad}, 1)
+    with pytest.raises(F.FleetError):
+        F.fleet_graph_build(sh, 2)           # batch above max_batch
+    with pytest.raises(F.FleetError):
+        F.fleet_graph_build(sh, 1, tile_m=24)
+
+
+# ------------------------------------------------------------------ paper tables
+def test_weight_size_table():
+    t = GOLD["weight_sizes"]
+    tile = t["tile"]
+    tot = tot_x = 0
+    for r in t["rows"]:
+        assert F.fleet_weight_bytes(r["K"], r["N"]) == r["weight_MiB"] << 20
+        assert F.fleet_weight_bytes_per_xcd(r["K"], r["N"], 8) == r["per_xcd_MiB"] << 20
+        assert F.fleet_l2_window_bytes(r["N"], 8, tile["T_N"], tile["T_K"]) == r["l2_window_KiB"] << 10
+        tot += F.fleet_weight_bytes(r["K"], r["N"])
+        tot_x += F.fleet_weight_bytes_per_xcd(r["K"], r["N"], 8)
+    assert tot == t["all_per_layer_MiB"] << 20 and tot_x == t["all_per_xcd_MiB"] << 20
+
+
+def test_l2_hit_model_and_effective_intensity():
+    m = GOLD["l2_hit_model"]
+    for c in m["cases"]:
+        assert F.fleet_l2_hit_model(c["batch"], m["T_M"], 32) == pytest.approx(c["hit"])
+    assert F.fleet_l2_hit_model(64, 16, 2) == pytest.approx(0.5)      # R capped by the workers
+    for c in GOLD["effective_intensity"]["cases"]:
+        assert F.fleet_effective_intensity(c["batch"], c["hit_percent"] / 100) == \
+            pytest.approx(c["ai_eff"], rel=5e-3)
+
+
+def test_step_bytes_accounting():
+    sh = si.qwen3_8b_shape(1, 1025).asdict()
+    per_layer = 368 << 20
+    lm = 151936 * 4096 * 2
+    kv = 36 * 2 * 8 * 128 * 2 * 1025
+    assert F.fleet_step_bytes(sh, 1, [1024]) == 36 * per_layer + lm + kv
+    sh64 = si.qwen3_8b_shape(64, 4097).asdict()
+    assert F.fleet_step_bytes(sh64, 64, [4096] * 64) == 36 * per_layer + lm + 64 * 36 * 4096 * 4097
+
+
+# ------------------------------------------------------------------ graph re-derivation
+BUF = dict(NONE=0, X=1, N=2, QKV=3, ATT=4, H=5, PART=6, HIDDEN_IN=7, TOKENS=8, KC=9, VC=10, POS=11,
+           HIDDEN_OUT=12, LOGITS=13)
+WK = dict(NONE=0, QKV=1, O=2, GU=3, DOWN=4, LM=5, LN1=6, LN2=7, FINAL=8, EMBED=9)
+INGEST, RMSNORM, GEMM, ATTN, MERGE, FINAL = range(6)
+
+
+def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m):
+    """Independent derivation of the serialized graph (same word layout)."""
+    H, hd, nq, nkv, Fd = sh.hidden, sh.head_dim, sh.n_q_heads, sh.n_kv_heads, sh.ffn
+    fma = batch <= 8
+    ur = 8 if fma else 16
+    tm = batch if fma else (tile_m or -(-batch // 16) * 16)
+    mt = -(-batch // tm)
+    S = 1
+    while S * 2 <= 32 and batch * nkv * S * 2 <= n_workers:
+        S *= 2
+    ops, tasks, events, queues, marks, xready = [], [], [], [[] for _ in range(n_xcd)], [], []
+    stage = [0]
+
+    def op(body, layer, epi, path, K, N, unit_rows, n_units, m_tiles, tile, inb, outb, aux, wk):
+        ops.append([body, layer, epi, path, K, N, unit_rows, n_units, m_tiles, tile, inb, outb, aux, wk,
+                    batch, 0])
+        return len(ops) - 1
+
+    def task(o, scope, xcd, a, wait, sig):
+        tasks.append([o, scope, xcd, *a, wait, sig, stage[0]] + [0] * 6)
+        return len(tasks) - 1
+
+    def cu_stage(o, items, wait):
+        ev = len(events)
+        events.append([len(items), 0, 0, len(items)])
+        if sched == 1:
+            first = len(tasks)
+            for key, a in items:
+                task(o, 1, -1, a, wait, ev)
+            for x in range(n_xcd):
+                queues[x].append([first, len(items), 2, stage[0]])
+        else:
+            for x in range(n_xcd):
+                mine = [a for key, a in items if key % n_xcd == x]
+                if mine:
+                    queues[x].append([len(tasks), len(mine), 1, stage[0]])
+                    for a in mine:
+                        task(o, 1, x, a, wait, ev)
+        stage[0] += 1
+        return ev
+
+    def gemm_stage(o, wait):
+        U, m_tiles = ops[o][7], ops[o][8]
+        ev = len(events)
+        if sched == 1:
+            cu = max(1, U // n_workers)
+            ng = -(-U // cu)
+            events.append([ng * m_tiles, 0, 0, ng * m_tiles])
+            first = len(tasks)
+            for m in range(m_tiles):
+                for g in range(ng):
+                    task(o, 1, -1, [g * cu, min(cu, U - g * cu), m, 0], wait, ev)
+            for x in range(n_xcd):
+                queues[x].append([first, ng * m_tiles, 2, stage[0]])
+        else:
+            bounds = [U * x // n_xcd for x in range(n_xcd + 1)]
+            owners = [x for x in range(n_xcd) if bounds[x + 1] > bounds[x]]
+            events.append([len(owners), 1, sum(1 << x for x in owners), len(owners)])
+            for x in owners:
+                t = task(o, 2, x, [bounds[x], bounds[x + 1] - bounds[x], 0, 0], wait, ev)
+                queues[x].append([t, 1, 0, stage[0]])
+        stage[0] += 1
+        return ev
+
+    def mark():
+        marks.append([len(q) for q in queues])
+
+    rows = [(b, [b, 0, 0, 0]) for b in range(batch)]
+    path = 0 if fma else 1
+    NQKV, QD = (nq + 2 * nkv) * hd, nq * hd
+    mark()
+    ev = cu_stage(op(INGEST, -1, 0, 0, H, H, 0, 0, 1, batch, BUF["HIDDEN_IN"], BUF["X"], 0, WK["EMBED"]), rows, -1)
+    xready.append(ev)
+    for l in range(sh.n_layers):
+        mark()
+        ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN1"]), rows, ev)
+        ev = gemm_stage(op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["N"], BUF["QKV"], 0, WK["QKV"]), ev)
+        att_items = [(p, [p // nkv, p % nkv, s, S]) for p in range(batch * nkv) for s in range(S)]
+        ev = cu_stage(op(ATTN, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["QKV"], BUF["PART"] if S > 1 else BUF["ATT"],
+                         S, WK["NONE"]), att_items, ev)
+        if S > 1:
+            mg = [(p, [p // nkv, p % nkv, 0, S]) for p in range(batch * nkv)]
+            ev = cu_stage(op(MERGE, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["PART"], BUF["ATT"], S, WK["NONE"]), mg, ev)
+        ev = gemm_stage(op(GEMM, l, 1, path, QD, H, ur, H // ur, mt, tm, BUF["ATT"], BUF["X"], 0, WK["O"]), ev)
+        ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN2"]), rows, ev)
+        ev = gemm_stage(op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["N"], BUF["H"], Fd, WK["GU"]), ev)
+        ev = gemm_stage(op(GEMM, l, 1, path, Fd, H, ur, H // ur, mt, tm, BUF["H"], BUF["X"], 0, WK["DOWN"]), ev)
+        xready.append(ev)
+    mark()
+    ev = cu_stage(op(FINAL, -1, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 1 if sh.vocab else 0, WK["FINAL"]),
+                  rows, ev)
+    if sh.vocab:
+        gemm_stage(op(GEMM, -1, 0, path, H, sh.vocab, ur, sh.vocab // ur, mt, tm, BUF["N"], BUF["LOGITS"], 0,
+                      WK["LM"]), ev)
+    mark()
+    qoff = np.cumsum([0] + [len(q) for q in queues])
+    return dict(ops=np.array(ops, np.int32), tasks=np.array(tasks, np.int32),
+                events=np.array(events, np.int32), qoff=qoff.astype(np.int32),
+                qents=np.array([e for q in queues for e in q], np.int32),
+                marks=np.array(marks, np.int32).T, xready=np.array(xready, np.int32),
+                S=S, tile_m=tm, m_tiles=mt)
+
+
+CASES = [
+    (si.reduced_shape(max_batch=64, n_layers=2, vocab=2064), [1, 5, 8, 9, 33, 64], 8, 256),
+    (si.qwen3_8b_shape(64, 4097, n_layers=3), [1, 8, 32, 64], 8, 256),
+    (si.reduced_shape(max_batch=4), [1, 3], 4, 120),          # another chiplet count / CU count
+]
+
+
+@pytest.mark.parametrize("sched,tile_m", [(0, 0), (0, 16), (1, 0), (1, 16)])
+def test_builder_equals_independent_derivation(sched, tile_m):
+    for sh, batches, n_xcd, n_workers in CASES:
+        for b in batches:
+            got = F.parse_graph(F.fleet_graph_build(sh.asdict(), b, n_xcd, n_workers, sched, tile_m))
+            exp = expected_graph(sh, b, n_xcd, n_workers, sched, tile_m)
+            for k in ("ops", "tasks", "events", "qoff", "qents", "marks", "xready"):
+                assert np.array_equal(got[k], exp[k]), (k, b, sched, tile_m)
+            h = got["header"]
+            assert (h["n_splits"], h["tile_m"], h["m_tiles"], h["batch"], h["sched"]) == \
+                (exp["S"], exp["tile_m"], exp["m_tiles"], b, sched)
+
+
+# ------------------------------------------------------------------ graph properties
+def _producers(g):
+    prod = {}
+    for i, t in enumerate(g["tasks"]):
+        prod.setdefault(int(t[8]), []).append(i)
+    return prod
+
+
+@pytest.mark.parametrize("sched", [0, 1])
+@pytest.mark.parametrize("batch", [1, 8, 32, 64])
+def test_graph_invariants(batch, sched):
+    sh = si.qwen3_8b_shape(64, 4097, n_layers=2)
+    g = F.parse_graph(F.fleet_graph_build(sh.asdict(), batch, 8, 256, sched, 16))
+    tasks, events, ops = g["tasks"], g["events"], g["ops"]
+    prod = _producers(g)
+    # thresholds: one device-level signal per chiplet for two-level events, per task otherwise
+    for e, ev in enumerate(events):
+        assert ev[0] == len(prod[e]) == ev[3]
+        if ev[1] == 1:
+            assert bin(int(ev[2])).count("1") == ev[0]
+            assert sorted(int(tasks[t][2]) for t in prod[e]) == [x for x in range(8) if ev[2] >> x & 1]
+    # every task is reachable from exactly one queue position (chiplet / XCD groups) or from
+    # the same position of every queue (device-wide groups)
+    seen = np.zeros(len(tasks), int)
+    for x in range(8):
+        for q in g["qents"][g["qoff"][x]:g["qoff"][x + 1]]:
+            first, cnt, dist = int(q[0]), int(q[1]), int(q[2])
+            if dist == 2:
+                seen[first:first + cnt] += 1
+            else:
+                seen[first:first + cnt] += 8
+                assert all(tasks[t][2] == x for t in range(first, first + cnt))
+    assert (seen == 8).all()
+    # queues list stages in dependency order: a task's wait event is signalled only by tasks
+    # of an earlier stage, and stages never decrease along a queue
+    for t in tasks:
+        if t[7] >= 0:
+            assert all(tasks[p][9] < t[9] for p in prod[int(t[7])])
+    for x in range(8):
+        st = g["qents"][g["qoff"][x]:g["qoff"][x + 1], 3]
+        assert (np.diff(st) > 0).all()
+    # GEMM device-tasks tile the output exactly once
+    for o, op in enumerate(ops):
+        if op[0] != GEMM:
+            continue
+        cover = np.zeros((op[7], op[8]), int)
+        for t in tasks[tasks[:, 0] == o]:
+            if t[1] == 2:
+                cover[t[3]:t[3] + t[4], :] += 1
+            else:
+                cover[t[3]:t[3] + t[4], t[5]] += 1
+        assert (cover == 1).all()
+        assert op[8] == -(-batch // op[9]) and op[5] == op[6] * op[7]
+
+
+def test_paper_task_counts_and_partition_pointers():
+    """Fleet's graph at bs=1: one CU-task per norm and eight chiplet-tasks per GEMM; the
+    partition of chiplet k starts k*(N/8) rows into the weight matrix."""
+    sh = si.qwen3_8b_shape(1, 1025, n_layers=1)
+    g = F.parse_graph(F.fleet_graph_build(sh.asdict(), 1, 8, 256, 0, 0))
+    tasks, ops = g["tasks"], g["ops"]
+    want = GOLD["tasks_per_op_bs1"]
+    by_wk = {int(op[13]): i for i, op in enumerate(ops)}
+    for name, wk in (("qkv", WK["QKV"]), ("o_proj", WK["O"]), ("gate_up", WK["GU"]), ("down", WK["DOWN"])):
+        mine = tasks[tasks[:, 0] == by_wk[wk]]
+        assert len(mine) == want[name] and (mine[:, 1] == 2).all()
+        op = ops[by_wk[wk]]
+        rows_per_xcd = op[5] // GOLD["partition_pointer_rule"]["n_xcd"]
+        for k, t in enumerate(mine):
+            assert t[2] == k and t[3] * op[6] == k * rows_per_xcd and t[4] * op[6] == rows_per_xcd
+    for wk in (WK["LN1"], WK["LN2"]):
+        assert (tasks[:, 0] == by_wk[wk]).sum() == want["rmsnorm"]
+    # m_tiles of the paper's 16-row tiles: 1 up to batch 16, 2 at 32, 4 at 64
+    sh64 = si.qwen3_8b_shape(64, 4097, n_layers=1)
+    for c in GOLD["l2_hit_model"]["cases"]:
+        if c["batch"] > 8:
+            h = F.parse_graph(F.fleet_graph_build(sh64.asdict(), c["batch"], 8, 256, 0, 16))["header"]
+            assert h["m_tiles"] == c["m_tiles"]
