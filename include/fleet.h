@@ -51,7 +51,11 @@ enum fleet_sched {
 enum fleet_flags {
   FLEET_FLAG_TRACE = 1,        /* record per-task tickets and timestamps               */
   FLEET_FLAG_SINGLE_LEVEL = 2, /* every worker signals the device counter itself       */
-  FLEET_FLAG_CHAINED = 8       /* fleet_gemm: rep i+1 waits for rep i's event          */
+  FLEET_FLAG_SEPARATE_NORM = 4,/* RMSNorm as CU-tasks also at batch <= 8 (default there:
+                                  fused into the consuming GEMV); fleet_gemm: activations
+                                  read from global memory instead of an LDS copy        */
+  FLEET_FLAG_CHAINED = 8,      /* fleet_gemm: rep i+1 waits for rep i's event          */
+  FLEET_FLAG_TIMING = 16       /* record per-task timestamps only (no tickets: cheaper) */
 };
 
 typedef struct {
@@ -175,10 +179,12 @@ int fleet_graph_build(const fleet_shape_t *shape, int32_t batch, int32_t n_xcd,
 int fleet_graph_dump(fleet_t *f, int32_t batch, void *buf, size_t *len);
 
 /*
- * fleet_trace_read (needs FLEET_FLAG_TRACE): copy the last step's execution
- * records to host memory after synchronising the device.  Each record is 8
- * int32 words: task, worker (workgroup id), xcd, tiles done, start ticket, end
- * ticket, start time, end time (100 MHz ticks relative to the first record).
+ * fleet_trace_read (needs FLEET_FLAG_TRACE or FLEET_FLAG_TIMING): copy the last
+ * step's execution records to host memory after synchronising the device.  Each
+ * record is 8 int32 words: task, worker (workgroup id), xcd, time the task was
+ * entered (before its wait), start ticket, end ticket (0 with FLEET_FLAG_TIMING),
+ * start time (after the wait), end time; times in 100 MHz ticks relative to the
+ * earliest start in the buffer.
  * Tickets come from one device-wide counter, so "end ticket of a predecessor <
  * start ticket of a successor" checks the dependency order (paper section 3.1).
  */

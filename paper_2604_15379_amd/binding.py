@@ -16,7 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libfleet.so")
 
 SCHED_COOPERATIVE, SCHED_UNAWARE = 0, 1
-FLAG_TRACE, FLAG_SINGLE_LEVEL, FLAG_CHAINED = 1, 2, 8
+FLAG_TRACE, FLAG_SINGLE_LEVEL, FLAG_SEPARATE_NORM, FLAG_CHAINED, FLAG_TIMING = 1, 2, 4, 8, 16
 
 EXPORTS = (
     "fleet_create", "fleet_decode_step", "fleet_decode_layers", "fleet_destroy", "fleet_gemm",
@@ -192,7 +192,7 @@ def fleet_graph_dump(f: Fleet, batch: int) -> np.ndarray:
 
 
 def fleet_trace_read(f: Fleet) -> np.ndarray:
-    """[n_records, 8] int32: task, worker, xcd, tiles, ticket0, ticket1, t0, t1."""
+    """[n_records, 8] int32: task, worker, xcd, t_enter, ticket0, ticket1, t0, t1."""
     return _sized_call(load_library().fleet_trace_read, f.handle).reshape(-1, 8)
 
 
@@ -246,7 +246,7 @@ HEADER_WORDS, OP_WORDS, TASK_WORDS, EVENT_WORDS, QENT_WORDS = 32, 16, 16, 4, 4
 H_NAMES = ("magic", "version", "n_ops", "n_tasks", "n_events", "n_xcd", "n_qent", "n_layers",
            "batch", "sched", "tile_m", "path", "n_splits", "n_workers", "m_tiles", "total_words")
 O_NAMES = ("body", "layer", "epi", "path", "K", "N", "unit_rows", "n_units", "m_tiles", "tile_m",
-           "in_buf", "out_buf", "aux", "wkind", "batch", "reserved")
+           "in_buf", "out_buf", "aux", "wkind", "batch", "aux2")
 T_NAMES = ("op", "scope", "xcd", "a0", "a1", "a2", "a3", "wait_event", "signal_event", "stage")
 
 

@@ -19,7 +19,7 @@ namespace {
 
 using namespace fleetg;
 
-constexpr size_t LDS_BYTES = 96 * 1024;   // > half of a CU's 160 KB: one worker per CU
+constexpr size_t LDS_BYTES = 128 * 1024;  // > half of a CU's 160 KB: one worker per CU
 constexpr int TRACE_CAP = 2048;           // records per worker
 
 struct DevInfo {
@@ -30,12 +30,11 @@ struct DevInfo {
 struct DevGraph {
   Graph g;
   int32_t *ops = nullptr, *tasks = nullptr, *events = nullptr, *qoff = nullptr, *qents = nullptr;
-  const void** op_w = nullptr;
-  const void** op_w2 = nullptr;
+  int32_t* fat = nullptr;   // [n_tasks][FAT_WORDS]: task words, op words, weight pointers, id
   uint32_t* ctr = nullptr;
   int ctr_words = 0;
   ~DevGraph() {
-    for (void* p : {(void*)ops, (void*)tasks, (void*)events, (void*)qoff, (void*)qents, (void*)op_w, (void*)op_w2, (void*)ctr})
+    for (void* p : {(void*)ops, (void*)tasks, (void*)events, (void*)qoff, (void*)qents, (void*)fat, (void*)ctr})
       if (p) (void)hipFree(p);
   }
 };
@@ -59,6 +58,30 @@ int upload(T** dst, const void* src, size_t bytes) {
   return FLEET_OK;
 }
 
+// the persistent kernel compiled for one GEMM flavour (see dev::N_VARIANTS)
+const void* kernel_variant(int v) {
+  switch (v) {
+    case 0: return (const void*)fleet_persistent_kernel<0>;
+    case 1: return (const void*)fleet_persistent_kernel<1>;
+    case 2: return (const void*)fleet_persistent_kernel<2>;
+    case 3: return (const void*)fleet_persistent_kernel<3>;
+    case 4: return (const void*)fleet_persistent_kernel<4>;
+    case 5: return (const void*)fleet_persistent_kernel<5>;
+    default: return (const void*)fleet_persistent_kernel<6>;
+  }
+}
+// variant for a graph: FMA path by batch (1, 2, 4, 8), MFMA path by tile height
+int variant_for(int path, int batch, int tile_m) {
+  if (path == P_FMA) return batch <= 1 ? 0 : batch <= 2 ? 1 : batch <= 4 ? 2 : 3;
+  return tile_m <= 16 ? 4 : tile_m <= 32 ? 5 : 6;
+}
+int launch_persistent(const Graph& g, dev::Params& P, int n_cu, hipStream_t st) {
+  const int v = variant_for(g.header[H_PATH], g.header[H_BATCH], g.header[H_TILE_M]);
+  void* args[] = {(void*)&P};
+  HIP_TRY(hipLaunchKernel(kernel_variant(v), dim3(n_cu), dim3(dev::WG), args, LDS_BYTES, st));
+  return FLEET_OK;
+}
+
 int prepare_kernel() {
   static bool done = false;
   if (done) return FLEET_OK;
@@ -66,10 +89,11 @@ int prepare_kernel() {
   HIP_TRY(hipGetDevice(&dev_id));
   HIP_TRY(hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev_id));
   if ((size_t)lds < LDS_BYTES + 4096) return FLEET_EDEVICE;
-  HIP_TRY(hipFuncSetAttribute((const void*)fleet_persistent_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES));
+  for (int v = 0; v < dev::N_VARIANTS; ++v)
+    HIP_TRY(hipFuncSetAttribute(kernel_variant(v), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES));
   HIP_TRY(hipFuncSetAttribute((const void*)fleet_probe_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES));
   int per_cu = 0;
-  HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fleet_persistent_kernel, dev::WG, LDS_BYTES));
+  HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fleet_persistent_kernel<6>, dev::WG, LDS_BYTES));
   if (per_cu < 1) return FLEET_EDEVICE;
   done = true;
   return FLEET_OK;
@@ -159,11 +183,27 @@ int upload_graph(DevGraph* dg, const fleet* f, const void* const* gemm_copies, i
     if (o[O_BODY] == B_ATTN && f) { w[i] = f->q_norm[o[O_LAYER]]; w2[i] = f->k_norm[o[O_LAYER]]; continue; }
     const void* second = nullptr;
     w[i] = f || gemm_copies ? resolve_weight(f, o[O_WKIND], o[O_LAYER], gemm_copies, &second) : nullptr;
+    if (o[O_BODY] == B_GEMM && (o[O_AUX2] & 0xff) != W_NONE && f) {   // gain of the fused RMSNorm
+      const void* unused = nullptr;
+      second = resolve_weight(f, o[O_AUX2] & 0xff, o[O_LAYER], nullptr, &unused);
+    }
     w2[i] = second;
   }
-  if ((rc = upload(&dg->op_w, w.data(), w.size() * sizeof(void*)))) return rc;
-  if ((rc = upload(&dg->op_w2, w2.data(), w2.size() * sizeof(void*)))) return rc;
-  dg->ctr_words = dev::C_EVENTS + g.n_events() * (1 + n_xcd);
+  // one self-contained descriptor per task, so that a worker fetches it with one read
+  std::vector<int32_t> fat((size_t)g.n_tasks() * dev::FAT_WORDS, 0);
+  for (int t = 0; t < g.n_tasks(); ++t) {
+    int32_t* d = &fat[(size_t)t * dev::FAT_WORDS];
+    const int32_t* tw = &g.tasks[(size_t)t * TASK_WORDS];
+    memcpy(d, tw, TASK_WORDS * 4);
+    memcpy(d + TASK_WORDS, &g.ops[(size_t)tw[T_OP] * OP_WORDS], OP_WORDS * 4);
+    memcpy(d + dev::FAT_W, &w[tw[T_OP]], sizeof(void*));
+    memcpy(d + dev::FAT_W2, &w2[tw[T_OP]], sizeof(void*));
+    d[dev::FAT_ID] = t;
+  }
+  if ((rc = upload(&dg->fat, fat.data(), fat.size() * 4))) return rc;
+  // G[e], L[x][e], then one arrival counter per (sequence, kv head) for the split-KV merge
+  // and the XCD-local wait relay words LW[x][e]
+  dg->ctr_words = dev::C_EVENTS + g.n_events() * (1 + 2 * n_xcd) + dev::N_PAIR;
   if ((rc = upload(&dg->ctr, nullptr, (size_t)dg->ctr_words * 4))) return rc;
   return FLEET_OK;
 }
@@ -179,14 +219,12 @@ int launch(dev::Params& P, const DevGraph* dg, int n_cu, int preset_event, hipSt
   }
   hipLaunchKernelGGL(fleet_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, st, dg->ctr, words, preset_word,
                      preset_val, P.status);
-  hipLaunchKernelGGL(fleet_persistent_kernel, dim3(n_cu), dim3(dev::WG), LDS_BYTES, st, P);
-  HIP_TRY(hipGetLastError());
-  return FLEET_OK;
+  return launch_persistent(dg->g, P, n_cu, st);
 }
 
 void fill_graph_params(dev::Params& P, const DevGraph* dg) {
   P.ops = dg->ops; P.tasks = dg->tasks; P.events = dg->events; P.qoff = dg->qoff; P.qents = dg->qents;
-  P.op_w = dg->op_w; P.op_w2 = dg->op_w2; P.ctr = dg->ctr; P.n_events = dg->g.n_events();
+  P.fat = dg->fat; P.ctr = dg->ctr; P.n_events = dg->g.n_events();
 }
 
 int get_graph(fleet* f, int batch, DevGraph** out) {
@@ -217,7 +255,7 @@ int run_layers(fleet* f, int batch, int layer_begin, int layer_end, bool with_in
   P.buf[BUF_PART] = f->part; P.buf[BUF_HIDDEN_IN] = (void*)hidden_in; P.buf[BUF_TOKENS] = (void*)tokens;
   P.buf[BUF_KC] = k_cache; P.buf[BUF_VC] = v_cache; P.buf[BUF_POS] = (void*)positions;
   P.buf[BUF_HIDDEN_OUT] = hidden_out; P.buf[BUF_LOGITS] = logits;
-  P.status = f->status; P.trace = (f->shape.flags & FLEET_FLAG_TRACE) ? f->trace : nullptr; P.trace_cap = TRACE_CAP;
+  P.status = f->status; P.trace = (f->shape.flags & (FLEET_FLAG_TRACE | FLEET_FLAG_TIMING)) ? f->trace : nullptr; P.trace_cap = TRACE_CAP;
   P.rope = f->rope; P.timeout_ticks = f->timeout_ticks; P.n_xcd = nx; P.flags = f->shape.flags;
   P.nq = f->shape.n_q_heads; P.nkv = f->shape.n_kv_heads; P.hd = f->shape.head_dim; P.max_batch = f->shape.max_batch;
   P.max_seq = f->shape.max_seq; P.hidden = f->shape.hidden; P.ffn = f->shape.ffn; P.batch = batch; P.eps = f->shape.rms_eps; P.vocab = f->shape.vocab;
@@ -292,7 +330,7 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
   if ((rc = upload(&f->part, nullptr, mb * shape->n_kv_heads * 32 * grp * dev::PART_STRIDE * 4))) return rc;
   if ((rc = upload(&f->status, nullptr, dev::ST_WORDS * 4))) return rc;
   HIP_TRY(hipMemset(f->status, 0, dev::ST_WORDS * 4));
-  if (shape->flags & FLEET_FLAG_TRACE)
+  if (shape->flags & (FLEET_FLAG_TRACE | FLEET_FLAG_TIMING))
     if ((rc = upload(&f->trace, nullptr, ((size_t)f->info.n_cu * TRACE_CAP * 8 + f->info.n_cu) * 4))) return rc;
   // rotary table: angle = pos * theta^(-2i/d), evaluated in double
   {
@@ -404,7 +442,11 @@ int fleet_trace_read(fleet_t* f, void* buf, size_t* len) {
   }
   int32_t t0 = 0x7fffffff;
   for (size_t i = 0; i < out.size(); i += 8) t0 = std::min(t0, out[i + 6]);
-  for (size_t i = 0; i < out.size(); i += 8) { out[i + 6] -= t0; out[i + 7] -= t0; }
+  const bool timing = !(f->shape.flags & FLEET_FLAG_TRACE);   // words 4, 5 are times too
+  for (size_t i = 0; i < out.size(); i += 8) {
+    out[i + 3] -= t0; out[i + 6] -= t0; out[i + 7] -= t0;
+    if (timing) { out[i + 4] -= t0; out[i + 5] -= t0; }
+  }
   const size_t need = out.size() * 4;
   if (!buf || *len < need) { *len = need; return buf ? FLEET_ESMALL : FLEET_OK; }
   memcpy(buf, out.data(), need);
@@ -442,9 +484,10 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const
     const int words = dg.ctr_words;
     hipLaunchKernelGGL(fleet_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, st, dg.ctr, words, -1, 0u, status);
     (void)hipEventRecord(e0, st);
-    hipLaunchKernelGGL(fleet_persistent_kernel, dim3(info.n_cu), dim3(dev::WG), LDS_BYTES, st, P);
+    int lrc = launch_persistent(dg.g, P, info.n_cu, st);
     (void)hipEventRecord(e1, st);
-    he = hipEventSynchronize(e1);
+    if (lrc) he = hipErrorLaunchFailure;
+    if (he == hipSuccess) he = hipEventSynchronize(e1);
     if (he == hipSuccess && elapsed_ms) he = hipEventElapsedTime(elapsed_ms, e0, e1);
   }
   int32_t code[dev::ST_WORDS] = {0};

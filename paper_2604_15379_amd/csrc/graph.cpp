@@ -17,11 +17,12 @@ struct Builder {
   Builder(int nx, int nw, int sc, int b) : n_xcd(nx), n_workers(nw), sched(sc), batch(b), queues(nx) {}
 
   int add_op(Body body, int layer, Epi epi, Path path, int K, int N, int unit_rows, int n_units,
-             int m_tiles, int tile_m, Buf in, Buf out, int aux, WKind wk) {
+             int m_tiles, int tile_m, Buf in, Buf out, int aux, WKind wk, int aux2 = 0) {
     int32_t w[OP_WORDS] = {0};
     w[O_BODY] = body; w[O_LAYER] = layer; w[O_EPI] = epi; w[O_PATH] = path; w[O_K] = K; w[O_N] = N;
     w[O_UNIT_ROWS] = unit_rows; w[O_N_UNITS] = n_units; w[O_M_TILES] = m_tiles; w[O_TILE_M] = tile_m;
     w[O_IN_BUF] = in; w[O_OUT_BUF] = out; w[O_AUX] = aux; w[O_WKIND] = wk; w[O_BATCH] = batch;
+    w[O_AUX2] = aux2;
     g.ops.insert(g.ops.end(), w, w + OP_WORDS);
     return g.n_ops() - 1;
   }
@@ -191,36 +192,49 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   int ev = b.cu_stage(op_in, batch, -1, row_key, row_arg);
   b.g.xready.push_back(ev);
 
+  // FMA path: the RMSNorm is fused into the GEMV that consumes it (every worker
+  // normalises the L2-resident residual rows into LDS); MFMA path: CU-task per row
+  const bool fuse_norm = path == P_FMA && !(s.flags & FLEET_FLAG_SEPARATE_NORM) &&
+                         (int64_t)batch * H * 2 <= GEMV_LDS_X_BYTES;
+  auto xmode = [&](int K) { return path == P_FMA && (int64_t)batch * K * 2 <= GEMV_LDS_X_BYTES ? X_LDS_COPY : X_GLOBAL; };
+
   for (int l = 0; l < s.n_layers; ++l) {
     b.mark_all();
-    int op_n1 = b.add_op(B_RMSNORM, l, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N, 0, W_LN1);
-    ev = b.cu_stage(op_n1, batch, ev, row_key, row_arg);
-
-    int op_qkv = b.add_op(B_GEMM, l, E_STORE_F32, path, H, NQKV, ur, NQKV / ur, mt, tm, BUF_N, BUF_QKV, 0, W_QKV);
+    int op_qkv;
+    if (fuse_norm) {
+      op_qkv = b.add_op(B_GEMM, l, E_STORE_F32, path, H, NQKV, ur, NQKV / ur, mt, tm, BUF_X, BUF_QKV, 0, W_QKV,
+                        W_LN1 | (X_LDS_NORM << 8));
+    } else {
+      int op_n1 = b.add_op(B_RMSNORM, l, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N, 0, W_LN1);
+      ev = b.cu_stage(op_n1, batch, ev, row_key, row_arg);
+      op_qkv = b.add_op(B_GEMM, l, E_STORE_F32, path, H, NQKV, ur, NQKV / ur, mt, tm, BUF_N, BUF_QKV, 0, W_QKV,
+                        xmode(H) << 8);
+    }
     ev = b.gemm_stage(op_qkv, ev);
 
-    int op_att = b.add_op(B_ATTN, l, E_STORE_F32, P_FMA, hd, QD, 0, 0, 1, batch, BUF_QKV,
-                          S > 1 ? BUF_PART : BUF_ATT, S, W_NONE);
+    // split-KV attention; the split that finishes last merges (no merge stage)
+    int op_att = b.add_op(B_ATTN, l, E_STORE_F32, P_FMA, hd, QD, 0, 0, 1, batch, BUF_QKV, BUF_ATT, S, W_NONE);
     ev = b.cu_stage(op_att, batch * nkv * S, ev,
                     [S](int i) { return i / S; },
                     [S, nkv](int i, int* a) { int p = i / S; a[0] = p / nkv; a[1] = p % nkv; a[2] = i % S; a[3] = S; });
-    if (S > 1) {
-      int op_mg = b.add_op(B_MERGE, l, E_STORE_F32, P_FMA, hd, QD, 0, 0, 1, batch, BUF_PART, BUF_ATT, S, W_NONE);
-      ev = b.cu_stage(op_mg, batch * nkv, ev, row_key,
-                      [S, nkv](int i, int* a) { a[0] = i / nkv; a[1] = i % nkv; a[2] = 0; a[3] = S; });
-    }
-    int op_o = b.add_op(B_GEMM, l, E_RESID_F32, path, QD, H, ur, H / ur, mt, tm, BUF_ATT, BUF_X, 0, W_O);
-    ev = b.gemm_stage(op_o, ev);
 
-    int op_n2 = b.add_op(B_RMSNORM, l, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N, 0, W_LN2);
-    ev = b.cu_stage(op_n2, batch, ev, row_key, row_arg);
+    int op_o = b.add_op(B_GEMM, l, E_RESID_F32, path, QD, H, ur, H / ur, mt, tm, BUF_ATT, BUF_X, 0, W_O, xmode(QD) << 8);
+    ev = b.gemm_stage(op_o, ev);
 
     // gate | up rows of one concatenated matrix; a unit is ur gate rows plus the
     // matching ur up rows (aux = row offset of the up half), SwiGLU in the epilogue
-    int op_gu = b.add_op(B_GEMM, l, E_SWIGLU_BF16, path, H, F, ur, F / ur, mt, tm, BUF_N, BUF_H, F, W_GU);
+    int op_gu;
+    if (fuse_norm) {
+      op_gu = b.add_op(B_GEMM, l, E_SWIGLU_BF16, path, H, F, ur, F / ur, mt, tm, BUF_X, BUF_H, F, W_GU,
+                       W_LN2 | (X_LDS_NORM << 8));
+    } else {
+      int op_n2 = b.add_op(B_RMSNORM, l, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N, 0, W_LN2);
+      ev = b.cu_stage(op_n2, batch, ev, row_key, row_arg);
+      op_gu = b.add_op(B_GEMM, l, E_SWIGLU_BF16, path, H, F, ur, F / ur, mt, tm, BUF_N, BUF_H, F, W_GU, xmode(H) << 8);
+    }
     ev = b.gemm_stage(op_gu, ev);
 
-    int op_dn = b.add_op(B_GEMM, l, E_RESID_F32, path, F, H, ur, H / ur, mt, tm, BUF_H, BUF_X, 0, W_DOWN);
+    int op_dn = b.add_op(B_GEMM, l, E_RESID_F32, path, F, H, ur, H / ur, mt, tm, BUF_H, BUF_X, 0, W_DOWN, xmode(F) << 8);
     ev = b.gemm_stage(op_dn, ev);
     b.g.xready.push_back(ev);
   }
@@ -232,7 +246,7 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   ev = b.cu_stage(op_fin, batch, ev, row_key, row_arg);
   if (s.vocab > 0) {
     int op_lm = b.add_op(B_GEMM, -1, E_STORE_F32, path, H, s.vocab, ur, s.vocab / ur, mt, tm, BUF_N,
-                         BUF_LOGITS, 0, W_LM);
+                         BUF_LOGITS, 0, W_LM, xmode(H) << 8);
     ev = b.gemm_stage(op_lm, ev);
   }
   b.mark_all();
@@ -250,8 +264,10 @@ Graph build_gemm_graph(int B, int K, int N, int sched_mode, int tile_m, int flag
   b.mark_all();
   b.mark_all();
   for (int r = 0; r < reps; ++r) {
+    const int xm = path == P_FMA && (int64_t)B * K * 2 <= GEMV_LDS_X_BYTES && !(flags & FLEET_FLAG_SEPARATE_NORM)
+                       ? X_LDS_COPY : X_GLOBAL;
     int op = b.add_op(B_GEMM, r % std::max(1, n_copies), E_STORE_F32, path, K, N, ur, N / ur, mt, tm,
-                      BUF_GEMM_X, BUF_GEMM_Y, 0, W_GEMM_COPY);
+                      BUF_GEMM_X, BUF_GEMM_Y, 0, W_GEMM_COPY, xm << 8);
     int e = b.gemm_stage(op, (flags & 8) ? ev : -1);
     ev = e;
   }

@@ -35,7 +35,7 @@ enum {
   H_BATCH, H_SCHED, H_TILE_M, H_PATH, H_N_SPLITS, H_N_WORKERS, H_M_TILES, H_TOTAL_WORDS
 };
 
-enum Body { B_INGEST = 0, B_RMSNORM = 1, B_GEMM = 2, B_ATTN = 3, B_MERGE = 4, B_FINAL = 5 };
+enum Body { B_INGEST = 0, B_RMSNORM = 1, B_GEMM = 2, B_ATTN = 3, B_FINAL = 5 };
 enum Epi { E_STORE_F32 = 0, E_RESID_F32 = 1, E_SWIGLU_BF16 = 2 };
 enum Path { P_FMA = 0, P_MFMA = 1 };
 enum Scope { S_WAVE = 0, S_CU = 1, S_CHIPLET = 2 };
@@ -56,13 +56,16 @@ enum WKind {
 // op word indices
 enum {
   O_BODY = 0, O_LAYER, O_EPI, O_PATH, O_K, O_N, O_UNIT_ROWS, O_N_UNITS, O_M_TILES, O_TILE_M,
-  O_IN_BUF, O_OUT_BUF, O_AUX, O_WKIND, O_BATCH, O_RESERVED
+  O_IN_BUF, O_OUT_BUF, O_AUX, O_WKIND, O_BATCH, O_AUX2
 };
+// O_AUX2 of a GEMM op: low byte = WKind of the fused RMSNorm gain (W_NONE if none),
+// bits 8..9 = activation mode of the FMA path (XMode)
+enum XMode { X_GLOBAL = 0, X_LDS_COPY = 1, X_LDS_NORM = 2 };
+constexpr int GEMV_LDS_X_BYTES = 96 * 1024;   // LDS the FMA path may fill with activations
 // task word indices.  A0..A3 by body:
 //   GEMM chiplet-task : A0 first unit, A1 unit count            (tiles = units x m_tiles)
 //   GEMM CU-task      : A0 first unit, A1 unit count, A2 m-tile
 //   ATTN              : A0 batch row, A1 kv head, A2 split, A3 n_splits
-//   MERGE             : A0 batch row, A1 kv head, A3 n_splits
 //   INGEST/RMSNORM/FINAL : A0 batch row
 enum { T_OP = 0, T_SCOPE, T_XCD, T_A0, T_A1, T_A2, T_A3, T_WAIT_EVENT, T_SIGNAL_EVENT, T_STAGE };
 // event word indices: threshold counts device-level signals (XCDs for a

@@ -77,10 +77,11 @@ def test_step_bytes_accounting():
 BUF = dict(NONE=0, X=1, N=2, QKV=3, ATT=4, H=5, PART=6, HIDDEN_IN=7, TOKENS=8, KC=9, VC=10, POS=11,
            HIDDEN_OUT=12, LOGITS=13)
 WK = dict(NONE=0, QKV=1, O=2, GU=3, DOWN=4, LM=5, LN1=6, LN2=7, FINAL=8, EMBED=9)
-INGEST, RMSNORM, GEMM, ATTN, MERGE, FINAL = range(6)
+INGEST, RMSNORM, GEMM, ATTN, FINAL = 0, 1, 2, 3, 5
+LDS_X_BYTES = 96 * 1024      # activations the FMA path may keep in LDS
 
 
-def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m):
+def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0):
     """Independent derivation of the serialized graph (same word layout)."""
     H, hd, nq, nkv, Fd = sh.hidden, sh.head_dim, sh.n_q_heads, sh.n_kv_heads, sh.ffn
     fma = batch <= 8
@@ -93,9 +94,9 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m):
     ops, tasks, events, queues, marks, xready = [], [], [], [[] for _ in range(n_xcd)], [], []
     stage = [0]
 
-    def op(body, layer, epi, path, K, N, unit_rows, n_units, m_tiles, tile, inb, outb, aux, wk):
+    def op(body, layer, epi, path, K, N, unit_rows, n_units, m_tiles, tile, inb, outb, aux, wk, aux2=0):
         ops.append([body, layer, epi, path, K, N, unit_rows, n_units, m_tiles, tile, inb, outb, aux, wk,
-                    batch, 0])
+                    batch, aux2])
         return len(ops) - 1
 
     def task(o, scope, xcd, a, wait, sig):
@@ -153,27 +154,40 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m):
     mark()
     ev = cu_stage(op(INGEST, -1, 0, 0, H, H, 0, 0, 1, batch, BUF["HIDDEN_IN"], BUF["X"], 0, WK["EMBED"]), rows, -1)
     xready.append(ev)
+    # batch <= 8: RMSNorm fused into the consuming GEMV (activation mode 2, gain kind in the
+    # low byte of aux2); activations that fit LDS are copied there (mode 1), else mode 0
+    fuse = fma and not (flags & 4) and batch * H * 2 <= LDS_X_BYTES
+
+    def xm(K):
+        return (1 if fma and batch * K * 2 <= LDS_X_BYTES else 0) << 8
+
     for l in range(sh.n_layers):
         mark()
-        ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN1"]), rows, ev)
-        ev = gemm_stage(op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["N"], BUF["QKV"], 0, WK["QKV"]), ev)
+        if fuse:
+            o_qkv = op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["X"], BUF["QKV"], 0, WK["QKV"],
+                       WK["LN1"] | 2 << 8)
+        else:
+            ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN1"]), rows, ev)
+            o_qkv = op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["N"], BUF["QKV"], 0, WK["QKV"], xm(H))
+        ev = gemm_stage(o_qkv, ev)
         att_items = [(p, [p // nkv, p % nkv, s, S]) for p in range(batch * nkv) for s in range(S)]
-        ev = cu_stage(op(ATTN, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["QKV"], BUF["PART"] if S > 1 else BUF["ATT"],
-                         S, WK["NONE"]), att_items, ev)
-        if S > 1:
-            mg = [(p, [p // nkv, p % nkv, 0, S]) for p in range(batch * nkv)]
-            ev = cu_stage(op(MERGE, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["PART"], BUF["ATT"], S, WK["NONE"]), mg, ev)
-        ev = gemm_stage(op(GEMM, l, 1, path, QD, H, ur, H // ur, mt, tm, BUF["ATT"], BUF["X"], 0, WK["O"]), ev)
-        ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN2"]), rows, ev)
-        ev = gemm_stage(op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["N"], BUF["H"], Fd, WK["GU"]), ev)
-        ev = gemm_stage(op(GEMM, l, 1, path, Fd, H, ur, H // ur, mt, tm, BUF["H"], BUF["X"], 0, WK["DOWN"]), ev)
+        ev = cu_stage(op(ATTN, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["QKV"], BUF["ATT"], S, WK["NONE"]), att_items, ev)
+        ev = gemm_stage(op(GEMM, l, 1, path, QD, H, ur, H // ur, mt, tm, BUF["ATT"], BUF["X"], 0, WK["O"], xm(QD)), ev)
+        if fuse:
+            o_gu = op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["X"], BUF["H"], Fd, WK["GU"],
+                      WK["LN2"] | 2 << 8)
+        else:
+            ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN2"]), rows, ev)
+            o_gu = op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["N"], BUF["H"], Fd, WK["GU"], xm(H))
+        ev = gemm_stage(o_gu, ev)
+        ev = gemm_stage(op(GEMM, l, 1, path, Fd, H, ur, H // ur, mt, tm, BUF["H"], BUF["X"], 0, WK["DOWN"], xm(Fd)), ev)
         xready.append(ev)
     mark()
     ev = cu_stage(op(FINAL, -1, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 1 if sh.vocab else 0, WK["FINAL"]),
                   rows, ev)
     if sh.vocab:
         gemm_stage(op(GEMM, -1, 0, path, H, sh.vocab, ur, sh.vocab // ur, mt, tm, BUF["N"], BUF["LOGITS"], 0,
-                      WK["LM"]), ev)
+                      WK["LM"], xm(H)), ev)
     mark()
     qoff = np.cumsum([0] + [len(q) for q in queues])
     return dict(ops=np.array(ops, np.int32), tasks=np.array(tasks, np.int32),
@@ -190,12 +204,12 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("sched,tile_m", [(0, 0), (0, 16), (1, 0), (1, 16)])
-def test_builder_equals_independent_derivation(sched, tile_m):
+@pytest.mark.parametrize("sched,tile_m,flags", [(0, 0, 0), (0, 16, 0), (1, 0, 0), (1, 16, 0), (0, 0, 4), (1, 0, 4)])
+def test_builder_equals_independent_derivation(sched, tile_m, flags):
     for sh, batches, n_xcd, n_workers in CASES:
         for b in batches:
-            got = F.parse_graph(F.fleet_graph_build(sh.asdict(), b, n_xcd, n_workers, sched, tile_m))
-            exp = expected_graph(sh, b, n_xcd, n_workers, sched, tile_m)
+            got = F.parse_graph(F.fleet_graph_build(sh.asdict(), b, n_xcd, n_workers, sched, tile_m, flags))
+            exp = expected_graph(sh, b, n_xcd, n_workers, sched, tile_m, flags)
             for k in ("ops", "tasks", "events", "qoff", "qents", "marks", "xready"):
                 assert np.array_equal(got[k], exp[k]), (k, b, sched, tile_m)
             h = got["header"]
@@ -262,7 +276,7 @@ def test_paper_task_counts_and_partition_pointers():
     """Fleet's graph at bs=1: one CU-task per norm and eight chiplet-tasks per GEMM; the
     partition of chiplet k starts k*(N/8) rows into the weight matrix."""
     sh = si.qwen3_8b_shape(1, 1025, n_layers=1)
-    g = F.parse_graph(F.fleet_graph_build(sh.asdict(), 1, 8, 256, 0, 0))
+    g = F.parse_graph(F.fleet_graph_build(sh.asdict(), 1, 8, 256, 0, 0, F.FLAG_SEPARATE_NORM))
     tasks, ops = g["tasks"], g["ops"]
     want = GOLD["tasks_per_op_bs1"]
     by_wk = {int(op[13]): i for i, op in enumerate(ops)}

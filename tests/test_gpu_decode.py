@@ -40,7 +40,8 @@ def test_two_layers_ragged_positions_with_lm_head(batch):
 
 
 @pytest.mark.parametrize("sched,tile_m,flags", [(1, 0, 0), (0, 16, 0), (1, 16, 0),
-                                                 (0, 0, F.FLAG_SINGLE_LEVEL)])
+                                                 (0, 0, F.FLAG_SINGLE_LEVEL), (0, 0, F.FLAG_SEPARATE_NORM),
+                                                 (1, 0, F.FLAG_SEPARATE_NORM)])
 @pytest.mark.parametrize("batch", [3, 40])
 def test_schedules_agree_with_oracle(batch, sched, tile_m, flags):
     print(f"decode modes batch={batch} sched={sched} tile_m={tile_m} flags={flags}", flush=True)
