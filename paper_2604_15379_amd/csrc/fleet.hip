@@ -202,8 +202,8 @@ int upload_graph(DevGraph* dg, const fleet* f, const void* const* gemm_copies, i
   }
   if ((rc = upload(&dg->fat, fat.data(), fat.size() * 4))) return rc;
   // G[e], L[x][e], then one arrival counter per (sequence, kv head) for the split-KV merge
-  // and the XCD-local wait relay words LW[x][e]
-  dg->ctr_words = dev::C_EVENTS + g.n_events() * (1 + 2 * n_xcd) + dev::N_PAIR;
+  // and one relay word per worker on its own cache line
+  dg->ctr_words = dev::C_EVENTS + g.n_events() * (1 + n_xcd) + dev::N_PAIR + n_xcd * dev::RELAY_SLOTS * dev::RELAY_STRIDE;
   if ((rc = upload(&dg->ctr, nullptr, (size_t)dg->ctr_words * 4))) return rc;
   return FLEET_OK;
 }

@@ -153,10 +153,12 @@ int resolve_tile_m(int batch, int tile_m) {
   return tile_m;
 }
 
-int attention_splits(int batch, int n_kv_heads, int n_workers) {
+int attention_splits(int batch, int n_kv_heads, int n_workers, int max_seq) {
+  // as many splits as there are idle workers, but no split shorter than 128 cache slots
+  // (a split costs a fixed prologue and its partial has to be merged)
   int pairs = std::max(1, batch * n_kv_heads);
   int s = 1;
-  while (s * 2 <= 32 && pairs * s * 2 <= n_workers) s *= 2;
+  while (s * 2 <= 32 && pairs * s * 2 <= n_workers && s * 2 * 128 <= max_seq) s *= 2;
   return s;
 }
 
@@ -181,7 +183,7 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   const int ur = path == P_FMA ? 8 : 16;
   const int tm = resolve_tile_m(batch, s.tile_m);
   const int mt = (batch + tm - 1) / tm;
-  const int S = attention_splits(batch, nkv, n_workers);
+  const int S = attention_splits(batch, nkv, n_workers, s.max_seq);
 
   auto row_key = [](int i) { return i; };
   auto row_arg = [](int i, int* a) { a[0] = i; a[1] = a[2] = a[3] = 0; };

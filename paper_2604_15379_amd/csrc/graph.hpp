@@ -86,7 +86,7 @@ struct Graph {
 // tile_m actually used for `batch` (0 = whole batch rounded up to 16; FMA path: batch)
 int resolve_tile_m(int batch, int tile_m);
 // KV splits per (sequence, kv head)
-int attention_splits(int batch, int n_kv_heads, int n_workers);
+int attention_splits(int batch, int n_kv_heads, int n_workers, int max_seq);
 // validate a shape; returns FLEET_OK or FLEET_EINVAL
 int check_shape(const fleet_shape_t& s);
 
