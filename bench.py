@@ -36,6 +36,10 @@ def parse():
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--seed", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-sweep", action="store_true",
+                    help="isolated skinny-GEMM sweep at the Qwen3-8B shapes (one JSON line per case)")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="run only a plain copy of this many MiB (counter calibration under rocprofv3)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per step from rocprofv3 counters (reported as roofline.traffic)")
     return ap.parse_args()
@@ -72,6 +76,31 @@ def cpu_baseline(shape, w_dev, hidden_dev, batch, kv, seed):
                       f"{t_layers:.3f} s + {t_head:.3f} s, scaled to all layers and sequences"}
 
 
+def gemm_sweep(a):
+    """y = x W^T as back-to-back device-tasks of the persistent kernel; every rep reads a
+    different weight copy (more than 512 MB in rotation, so the 256 MB last-level cache
+    cannot serve the weights) and the launch is timed with HIP events by the library."""
+    import torch
+    import paper_2604_15379_amd as F
+    import synth_inputs as si
+    g = si.Gen(1, "cuda")
+    for (K, N) in ((4096, 6144), (4096, 4096), (4096, 24576), (12288, 4096)):
+        n_copies = max(2, -(-(640 << 20) // (K * N * 2)))
+        ws = [g.normal_bf16((N, K), 0.02) for _ in range(n_copies)]
+        for B in (1, 8, 32, 64):
+            x = g.normal_bf16((B, K), 1.0)
+            y = torch.empty((B, N), device="cuda", dtype=torch.float32)
+            reps = 4 * n_copies
+            F.fleet_gemm(B, K, N, x, ws, y, a.sched, a.tile_m, a.flags, reps)          # warm-up
+            ms = min(F.fleet_gemm(B, K, N, x, ws, y, a.sched, a.tile_m, a.flags, reps) for _ in range(3))
+            bytes_per_rep = K * N * 2 + B * (K * 2 + N * 4)
+            print(json.dumps({"gemm": [B, K, N], "us_per_gemm": ms * 1e3 / reps, "reps": reps,
+                              "GBps": bytes_per_rep * reps / (ms * 1e-3) / 1e9,
+                              "frac_of_8TBps": bytes_per_rep * reps / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                              "sched_mode": a.sched, "tile_m": a.tile_m, "flags": a.flags}), flush=True)
+        del ws
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -84,6 +113,19 @@ def main():
     import synth_inputs as si
 
     torch.cuda.set_device(0)
+    if a.calibrate_copy > 0:
+        n = a.calibrate_copy << 20
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(a.steps):
+            F.fleet_copy(dst, src, n, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.equal(src, dst)
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": a.steps}))
+        return
+    if a.gemm_sweep:
+        gemm_sweep(a)
+        return
     B = a.batch
     shape = si.qwen3_8b_shape(max_batch=B, max_seq=a.kv + 1, n_layers=a.layers)
     g = si.Gen(a.seed, "cuda")

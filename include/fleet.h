@@ -201,6 +201,14 @@ int fleet_last_status(fleet_t *f, fleet_status_t *out);
 int fleet_device_probe(int32_t n_blocks, int32_t *xcd_of_block);
 
 /*
+ * fleet_copy (measurement): a plain streaming copy of `bytes` (a multiple of 16) from
+ * src to dst, both device memory, on `stream`.  Its HBM traffic is known exactly
+ * (bytes read + bytes written), which calibrates the hardware traffic counters the
+ * roofline figures are checked against.
+ */
+int fleet_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+/*
  * Traffic accounting, closed forms (paper section 5.4, Table "weight sizes",
  * Eq. "l2-hit", Figure "roofline"): bytes are for bf16 weights.
  */

@@ -21,7 +21,7 @@ FLAG_TRACE, FLAG_SINGLE_LEVEL, FLAG_SEPARATE_NORM, FLAG_CHAINED, FLAG_TIMING = 1
 EXPORTS = (
     "fleet_create", "fleet_decode_step", "fleet_decode_layers", "fleet_destroy", "fleet_gemm",
     "fleet_graph_build", "fleet_graph_dump", "fleet_trace_read", "fleet_last_status",
-    "fleet_device_probe", "fleet_weight_bytes", "fleet_weight_bytes_per_xcd",
+    "fleet_device_probe", "fleet_copy", "fleet_weight_bytes", "fleet_weight_bytes_per_xcd",
     "fleet_l2_window_bytes", "fleet_l2_hit_model", "fleet_effective_intensity",
     "fleet_step_bytes", "fleet_strerror",
 )
@@ -212,6 +212,12 @@ def fleet_device_probe(n_blocks: int) -> np.ndarray:
     if rc != 0:
         raise FleetError(rc, "fleet_device_probe")
     return out
+
+
+def fleet_copy(dst, src, nbytes: int, stream=0) -> None:
+    rc = load_library().fleet_copy(_ptr(dst), _ptr(src), C.c_size_t(nbytes), C.c_void_p(stream))
+    if rc != 0:
+        raise FleetError(rc, "fleet_copy")
 
 
 def fleet_weight_bytes(K, N):

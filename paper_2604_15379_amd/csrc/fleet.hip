@@ -499,6 +499,13 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const
   return code[dev::ST_CODE];
 }
 
+int fleet_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || bytes == 0 || bytes % 16) return FLEET_EINVAL;
+  hipLaunchKernelGGL(fleet_copy_kernel, dim3(2048), dim3(256), 0, (hipStream_t)stream, (const u32x4*)src, (u32x4*)dst, bytes / 16);
+  HIP_TRY(hipGetLastError());
+  return FLEET_OK;
+}
+
 int64_t fleet_weight_bytes(int32_t K, int32_t N) { return (int64_t)K * N * 2; }
 int64_t fleet_weight_bytes_per_xcd(int32_t K, int32_t N, int32_t n_xcd) { return (int64_t)K * N * 2 / n_xcd; }
 int64_t fleet_l2_window_bytes(int32_t N, int32_t n_xcd, int32_t tile_n, int32_t tile_k) {

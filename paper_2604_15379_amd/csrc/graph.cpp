@@ -199,18 +199,22 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   const bool fuse_norm = path == P_FMA && !(s.flags & FLEET_FLAG_SEPARATE_NORM) &&
                          (int64_t)batch * H * 2 <= GEMV_LDS_X_BYTES;
   auto xmode = [&](int K) { return path == P_FMA && (int64_t)batch * K * 2 <= GEMV_LDS_X_BYTES ? X_LDS_COPY : X_GLOBAL; };
+  // weight blocks requested before the wait (bits 10..11 of aux2).  Measured at batch 1:
+  // requesting only one block after the short O-projection stage (to reach the poll
+  // sooner) is slower than requesting the full depth everywhere.
+  const int PRE2 = 3 << 10;
 
   for (int l = 0; l < s.n_layers; ++l) {
     b.mark_all();
     int op_qkv;
     if (fuse_norm) {
       op_qkv = b.add_op(B_GEMM, l, E_STORE_F32, path, H, NQKV, ur, NQKV / ur, mt, tm, BUF_X, BUF_QKV, 0, W_QKV,
-                        W_LN1 | (X_LDS_NORM << 8));
+                        W_LN1 | (X_LDS_NORM << 8) | PRE2);
     } else {
       int op_n1 = b.add_op(B_RMSNORM, l, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N, 0, W_LN1);
       ev = b.cu_stage(op_n1, batch, ev, row_key, row_arg);
       op_qkv = b.add_op(B_GEMM, l, E_STORE_F32, path, H, NQKV, ur, NQKV / ur, mt, tm, BUF_N, BUF_QKV, 0, W_QKV,
-                        xmode(H) << 8);
+                        (xmode(H) << 8) | PRE2);
     }
     ev = b.gemm_stage(op_qkv, ev);
 
@@ -220,7 +224,7 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
                     [S](int i) { return i / S; },
                     [S, nkv](int i, int* a) { int p = i / S; a[0] = p / nkv; a[1] = p % nkv; a[2] = i % S; a[3] = S; });
 
-    int op_o = b.add_op(B_GEMM, l, E_RESID_F32, path, QD, H, ur, H / ur, mt, tm, BUF_ATT, BUF_X, 0, W_O, xmode(QD) << 8);
+    int op_o = b.add_op(B_GEMM, l, E_RESID_F32, path, QD, H, ur, H / ur, mt, tm, BUF_ATT, BUF_X, 0, W_O, (xmode(QD) << 8) | PRE2);
     ev = b.gemm_stage(op_o, ev);
 
     // gate | up rows of one concatenated matrix; a unit is ur gate rows plus the
@@ -228,15 +232,15 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
     int op_gu;
     if (fuse_norm) {
       op_gu = b.add_op(B_GEMM, l, E_SWIGLU_BF16, path, H, F, ur, F / ur, mt, tm, BUF_X, BUF_H, F, W_GU,
-                       W_LN2 | (X_LDS_NORM << 8));
+                       W_LN2 | (X_LDS_NORM << 8) | PRE2);
     } else {
       int op_n2 = b.add_op(B_RMSNORM, l, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N, 0, W_LN2);
       ev = b.cu_stage(op_n2, batch, ev, row_key, row_arg);
-      op_gu = b.add_op(B_GEMM, l, E_SWIGLU_BF16, path, H, F, ur, F / ur, mt, tm, BUF_N, BUF_H, F, W_GU, xmode(H) << 8);
+      op_gu = b.add_op(B_GEMM, l, E_SWIGLU_BF16, path, H, F, ur, F / ur, mt, tm, BUF_N, BUF_H, F, W_GU, (xmode(H) << 8) | PRE2);
     }
     ev = b.gemm_stage(op_gu, ev);
 
-    int op_dn = b.add_op(B_GEMM, l, E_RESID_F32, path, F, H, ur, H / ur, mt, tm, BUF_H, BUF_X, 0, W_DOWN, xmode(F) << 8);
+    int op_dn = b.add_op(B_GEMM, l, E_RESID_F32, path, F, H, ur, H / ur, mt, tm, BUF_H, BUF_X, 0, W_DOWN, (xmode(F) << 8) | PRE2);
     ev = b.gemm_stage(op_dn, ev);
     b.g.xready.push_back(ev);
   }
@@ -248,7 +252,7 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   ev = b.cu_stage(op_fin, batch, ev, row_key, row_arg);
   if (s.vocab > 0) {
     int op_lm = b.add_op(B_GEMM, -1, E_STORE_F32, path, H, s.vocab, ur, s.vocab / ur, mt, tm, BUF_N,
-                         BUF_LOGITS, 0, W_LM, xmode(H) << 8);
+                         BUF_LOGITS, 0, W_LM, (xmode(H) << 8) | PRE2);
     ev = b.gemm_stage(op_lm, ev);
   }
   b.mark_all();
@@ -269,7 +273,7 @@ Graph build_gemm_graph(int B, int K, int N, int sched_mode, int tile_m, int flag
     const int xm = path == P_FMA && (int64_t)B * K * 2 <= GEMV_LDS_X_BYTES && !(flags & FLEET_FLAG_SEPARATE_NORM)
                        ? X_LDS_COPY : X_GLOBAL;
     int op = b.add_op(B_GEMM, r % std::max(1, n_copies), E_STORE_F32, path, K, N, ur, N / ur, mt, tm,
-                      BUF_GEMM_X, BUF_GEMM_Y, 0, W_GEMM_COPY, xm << 8);
+                      BUF_GEMM_X, BUF_GEMM_Y, 0, W_GEMM_COPY, (xm << 8) | (3 << 10));
     int e = b.gemm_stage(op, (flags & 8) ? ev : -1);
     ev = e;
   }

@@ -59,7 +59,8 @@ enum {
   O_IN_BUF, O_OUT_BUF, O_AUX, O_WKIND, O_BATCH, O_AUX2
 };
 // O_AUX2 of a GEMM op: low byte = WKind of the fused RMSNorm gain (W_NONE if none),
-// bits 8..9 = activation mode of the FMA path (XMode)
+// bits 8..9 = activation mode of the FMA path (XMode), bits 10..11 = weight blocks the FMA
+// path requests before its dependency wait (0..3)
 enum XMode { X_GLOBAL = 0, X_LDS_COPY = 1, X_LDS_NORM = 2 };
 constexpr int GEMV_LDS_X_BYTES = 96 * 1024;   // LDS the FMA path may fill with activations
 // task word indices.  A0..A3 by body:

@@ -158,14 +158,16 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
     # low byte of aux2); activations that fit LDS are copied there (mode 1), else mode 0
     fuse = fma and not (flags & 4) and batch * H * 2 <= LDS_X_BYTES
 
+    PRE = 3 << 10     # weight blocks the FMA path requests before its wait (bits 10..11)
+
     def xm(K):
-        return (1 if fma and batch * K * 2 <= LDS_X_BYTES else 0) << 8
+        return ((1 if fma and batch * K * 2 <= LDS_X_BYTES else 0) << 8) | PRE
 
     for l in range(sh.n_layers):
         mark()
         if fuse:
             o_qkv = op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["X"], BUF["QKV"], 0, WK["QKV"],
-                       WK["LN1"] | 2 << 8)
+                       WK["LN1"] | 2 << 8 | PRE)
         else:
             ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN1"]), rows, ev)
             o_qkv = op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["N"], BUF["QKV"], 0, WK["QKV"], xm(H))
@@ -175,7 +177,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
         ev = gemm_stage(op(GEMM, l, 1, path, QD, H, ur, H // ur, mt, tm, BUF["ATT"], BUF["X"], 0, WK["O"], xm(QD)), ev)
         if fuse:
             o_gu = op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["X"], BUF["H"], Fd, WK["GU"],
-                      WK["LN2"] | 2 << 8)
+                      WK["LN2"] | 2 << 8 | PRE)
         else:
             ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN2"]), rows, ev)
             o_gu = op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["N"], BUF["H"], Fd, WK["GU"], xm(H))
