@@ -323,10 +323,13 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
   const size_t QD = (size_t)shape->n_q_heads * shape->head_dim;
   const size_t grp = shape->n_q_heads / shape->n_kv_heads;
   if ((rc = upload(&f->x, nullptr, mb * H * 4))) return rc;
-  if ((rc = upload((char**)&f->n, nullptr, mb * H * 2))) return rc;
+  // bf16 activations: feature dimension padded to whole 256-wide chunks (the MFMA kernels
+  // store them chunk-tiled)
+  auto pad256 = [](size_t k) { return (k + 255) / 256 * 256; };
+  if ((rc = upload((char**)&f->n, nullptr, mb * pad256(H) * 2))) return rc;
   if ((rc = upload(&f->qkv, nullptr, mb * NQKV * 4))) return rc;
-  if ((rc = upload((char**)&f->att, nullptr, mb * QD * 2))) return rc;
-  if ((rc = upload((char**)&f->h, nullptr, mb * F * 2))) return rc;
+  if ((rc = upload((char**)&f->att, nullptr, mb * pad256(QD) * 2))) return rc;
+  if ((rc = upload((char**)&f->h, nullptr, mb * pad256(F) * 2))) return rc;
   if ((rc = upload(&f->part, nullptr, mb * shape->n_kv_heads * 32 * grp * dev::PART_STRIDE * 4))) return rc;
   if ((rc = upload(&f->status, nullptr, dev::ST_WORDS * 4))) return rc;
   HIP_TRY(hipMemset(f->status, 0, dev::ST_WORDS * 4));
