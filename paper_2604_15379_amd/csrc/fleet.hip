@@ -33,6 +33,8 @@ struct DevGraph {
   int32_t* fat = nullptr;   // [n_tasks][FAT_WORDS]: task words, op words, weight pointers, id
   uint32_t* ctr = nullptr;
   int ctr_words = 0;
+  // memo of wait_event_range for the last queue slice launched
+  int memo_begin[dev::MAX_XCD] = {-1, -1, -1, -1, -1, -1, -1, -1}, memo_end[dev::MAX_XCD] = {0}, memo_first = 0, memo_last = -1;
   ~DevGraph() {
     for (void* p : {(void*)ops, (void*)tasks, (void*)events, (void*)qoff, (void*)qents, (void*)fat, (void*)ctr})
       if (p) (void)hipFree(p);
@@ -75,8 +77,35 @@ int variant_for(int path, int batch, int tile_m) {
   if (path == P_FMA) return batch <= 1 ? 0 : batch <= 2 ? 1 : batch <= 4 ? 2 : 3;
   return tile_m <= 16 ? 4 : tile_m <= 32 ? 5 : 6;
 }
-int launch_persistent(const Graph& g, dev::Params& P, int n_cu, hipStream_t st) {
+// range of events that tasks of the launched queue slices wait for (stages of the slices)
+void wait_event_range(const Graph& g, dev::Params& P, int n_xcd) {
+  int lo = 1 << 30, hi = -1;
+  std::vector<char> stage_in;
+  for (int x = 0; x < n_xcd; ++x)
+    for (int qi = P.q_begin[x]; qi < P.q_end[x]; ++qi) {
+      const int32_t* e = &g.qents[((size_t)g.qoff[x] + qi) * QENT_WORDS];
+      for (int t = e[Q_FIRST]; t < e[Q_FIRST] + e[Q_COUNT]; ++t) {
+        const int w = g.tasks[(size_t)t * TASK_WORDS + T_WAIT_EVENT];
+        if (w >= 0) { lo = std::min(lo, w); hi = std::max(hi, w); }
+      }
+    }
+  P.first_wait_event = hi >= 0 ? lo : 0;
+  P.last_wait_event = hi;
+}
+
+int launch_persistent(DevGraph* dg, dev::Params& P, int n_cu, hipStream_t st) {
+  const Graph& g = dg->g;
   const int v = variant_for(g.header[H_PATH], g.header[H_BATCH], g.header[H_TILE_M]);
+  const int nx = g.header[H_N_XCD];
+  bool same = true;
+  for (int x = 0; x < nx; ++x) same = same && dg->memo_begin[x] == P.q_begin[x] && dg->memo_end[x] == P.q_end[x];
+  if (!same) {
+    wait_event_range(g, P, nx);
+    for (int x = 0; x < nx; ++x) { dg->memo_begin[x] = P.q_begin[x]; dg->memo_end[x] = P.q_end[x]; }
+    dg->memo_first = P.first_wait_event; dg->memo_last = P.last_wait_event;
+  } else {
+    P.first_wait_event = dg->memo_first; P.last_wait_event = dg->memo_last;
+  }
   void* args[] = {(void*)&P};
   HIP_TRY(hipLaunchKernel(kernel_variant(v), dim3(n_cu), dim3(dev::WG), args, LDS_BYTES, st));
   return FLEET_OK;
@@ -209,7 +238,7 @@ int upload_graph(DevGraph* dg, const fleet* f, const void* const* gemm_copies, i
 }
 
 // reset counters, then run queue slice [q_begin, q_end) of every XCD
-int launch(dev::Params& P, const DevGraph* dg, int n_cu, int preset_event, hipStream_t st) {
+int launch(dev::Params& P, DevGraph* dg, int n_cu, int preset_event, hipStream_t st) {
   const int words = dg->ctr_words;
   int preset_word = -1;
   uint32_t preset_val = 0;
@@ -219,7 +248,7 @@ int launch(dev::Params& P, const DevGraph* dg, int n_cu, int preset_event, hipSt
   }
   hipLaunchKernelGGL(fleet_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, st, dg->ctr, words, preset_word,
                      preset_val, P.status);
-  return launch_persistent(dg->g, P, n_cu, st);
+  return launch_persistent(dg, P, n_cu, st);
 }
 
 void fill_graph_params(dev::Params& P, const DevGraph* dg) {
@@ -487,7 +516,7 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const
     const int words = dg.ctr_words;
     hipLaunchKernelGGL(fleet_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, st, dg.ctr, words, -1, 0u, status);
     (void)hipEventRecord(e0, st);
-    int lrc = launch_persistent(dg.g, P, info.n_cu, st);
+    int lrc = launch_persistent(&dg, P, info.n_cu, st);
     (void)hipEventRecord(e1, st);
     if (lrc) he = hipErrorLaunchFailure;
     if (he == hipSuccess) he = hipEventSynchronize(e1);
