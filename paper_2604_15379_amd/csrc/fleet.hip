@@ -32,7 +32,7 @@ struct DevGraph {
   int32_t *ops = nullptr, *tasks = nullptr, *events = nullptr, *qoff = nullptr, *qents = nullptr;
   int32_t* fat = nullptr;   // [n_tasks][FAT_WORDS]: task words, op words, weight pointers, id
   uint32_t* ctr = nullptr;
-  int ctr_words = 0;
+  int ctr_words = 0, gcnt_base = 0;
   // memo of wait_event_range for the last queue slice launched
   int memo_begin[dev::MAX_XCD] = {-1, -1, -1, -1, -1, -1, -1, -1}, memo_end[dev::MAX_XCD] = {0}, memo_first = 0, memo_last = -1;
   ~DevGraph() {
@@ -57,6 +57,16 @@ int upload(T** dst, const void* src, size_t bytes) {
   if (bytes == 0) bytes = 16;
   HIP_TRY(hipMalloc((void**)dst, bytes));
   if (src) HIP_TRY(hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice));
+  return FLEET_OK;
+}
+
+// *dst = new device buffer holding the [rows][K] bf16 matrix `src` as MFMA operand blocks
+int pack_matrix(void** dst, const void* src, int rows, int K, bool by_unit) {
+  const int nrb = (rows + 15) / 16;
+  const size_t bytes = (size_t)nrb * 16 * K * 2;
+  HIP_TRY(hipMalloc(dst, bytes));
+  hipLaunchKernelGGL(fleet_pack_kernel, dim3(2048), dim3(256), 0, 0, (const u32x4*)src, (u32x4*)*dst, rows, nrb, K, by_unit ? 1 : 0);
+  HIP_TRY(hipGetLastError());
   return FLEET_OK;
 }
 
@@ -168,10 +178,14 @@ struct fleet {
   fleet_shape_t shape;
   std::vector<const void*> ln1, wqkv, q_norm, k_norm, wo, ln2, wgu, wdown;
   const void *embed = nullptr, *final_norm = nullptr, *lm_head = nullptr;
+  // library-owned copies of the GEMM weights in the operand-block layout of the MFMA
+  // kernels (made by fleet_create when max_batch reaches those kernels)
+  std::vector<void*> pk_qkv, pk_o, pk_gu, pk_down;
+  void* pk_lm = nullptr;
   DevInfo info;
   // scratch activations (device)
   float* x = nullptr; void* n = nullptr; float* qkv = nullptr; void* att = nullptr; void* h = nullptr;
-  float* part = nullptr; float2* rope = nullptr;
+  float* part = nullptr; float* gpart = nullptr; float2* rope = nullptr;
   int32_t* status = nullptr; int32_t* trace = nullptr;
   std::map<int, std::unique_ptr<DevGraph>> graphs;
   long long timeout_ticks = 0;
@@ -181,8 +195,19 @@ struct fleet {
 
 namespace {
 
-const void* resolve_weight(const fleet* f, int wkind, int layer, const void* const* gemm_copies, const void** second) {
+const void* resolve_weight(const fleet* f, int wkind, int layer, const void* const* gemm_copies, const void** second,
+                           bool packed = false) {
   *second = nullptr;
+  if (packed && f) {
+    switch (wkind) {
+      case W_QKV: return f->pk_qkv[layer];
+      case W_O: return f->pk_o[layer];
+      case W_GU: return f->pk_gu[layer];
+      case W_DOWN: return f->pk_down[layer];
+      case W_LM: return f->pk_lm;
+      default: break;
+    }
+  }
   switch (wkind) {
     case W_QKV: return f->wqkv[layer];
     case W_O: return f->wo[layer];
@@ -211,7 +236,7 @@ int upload_graph(DevGraph* dg, const fleet* f, const void* const* gemm_copies, i
     const int32_t* o = &g.ops[(size_t)i * OP_WORDS];
     if (o[O_BODY] == B_ATTN && f) { w[i] = f->q_norm[o[O_LAYER]]; w2[i] = f->k_norm[o[O_LAYER]]; continue; }
     const void* second = nullptr;
-    w[i] = f || gemm_copies ? resolve_weight(f, o[O_WKIND], o[O_LAYER], gemm_copies, &second) : nullptr;
+    w[i] = f || gemm_copies ? resolve_weight(f, o[O_WKIND], o[O_LAYER], gemm_copies, &second, o[O_PATH] == P_MFMA) : nullptr;
     if (o[O_BODY] == B_GEMM && (o[O_AUX2] & 0xff) != W_NONE && f) {   // gain of the fused RMSNorm
       const void* unused = nullptr;
       second = resolve_weight(f, o[O_AUX2] & 0xff, o[O_LAYER], nullptr, &unused);
@@ -232,7 +257,9 @@ int upload_graph(DevGraph* dg, const fleet* f, const void* const* gemm_copies, i
   if ((rc = upload(&dg->fat, fat.data(), fat.size() * 4))) return rc;
   // G[e], L[x][e], then one arrival counter per (sequence, kv head) for the split-KV merge
   // and one relay word per worker on its own cache line
-  dg->ctr_words = dev::C_EVENTS + g.n_events() * (1 + n_xcd) + dev::N_PAIR + n_xcd * dev::RELAY_SLOTS * dev::RELAY_STRIDE;
+  // (MFMA graphs: then the arrival counters of split-K GEMM tiles)
+  dg->gcnt_base = dev::C_EVENTS + g.n_events() * (1 + n_xcd) + dev::N_PAIR + n_xcd * dev::RELAY_SLOTS * dev::RELAY_STRIDE;
+  dg->ctr_words = dg->gcnt_base + (g.header[H_PATH] == P_MFMA ? dev::GEMM_CNT_WORDS : 0);
   if ((rc = upload(&dg->ctr, nullptr, (size_t)dg->ctr_words * 4))) return rc;
   return FLEET_OK;
 }
@@ -253,7 +280,7 @@ int launch(dev::Params& P, DevGraph* dg, int n_cu, int preset_event, hipStream_t
 
 void fill_graph_params(dev::Params& P, const DevGraph* dg) {
   P.ops = dg->ops; P.tasks = dg->tasks; P.events = dg->events; P.qoff = dg->qoff; P.qents = dg->qents;
-  P.fat = dg->fat; P.ctr = dg->ctr; P.n_events = dg->g.n_events();
+  P.fat = dg->fat; P.ctr = dg->ctr; P.n_events = dg->g.n_events(); P.gcnt_base = dg->gcnt_base;
 }
 
 int get_graph(fleet* f, int batch, DevGraph** out) {
@@ -281,7 +308,7 @@ int run_layers(fleet* f, int batch, int layer_begin, int layer_end, bool with_in
   memset(&P, 0, sizeof(P));
   fill_graph_params(P, dg);
   P.buf[BUF_X] = f->x; P.buf[BUF_N] = f->n; P.buf[BUF_QKV] = f->qkv; P.buf[BUF_ATT] = f->att; P.buf[BUF_H] = f->h;
-  P.buf[BUF_PART] = f->part; P.buf[BUF_HIDDEN_IN] = (void*)hidden_in; P.buf[BUF_TOKENS] = (void*)tokens;
+  P.buf[BUF_PART] = f->part; P.buf[BUF_GPART] = f->gpart; P.buf[BUF_HIDDEN_IN] = (void*)hidden_in; P.buf[BUF_TOKENS] = (void*)tokens;
   P.buf[BUF_KC] = k_cache; P.buf[BUF_VC] = v_cache; P.buf[BUF_POS] = (void*)positions;
   P.buf[BUF_HIDDEN_OUT] = hidden_out; P.buf[BUF_LOGITS] = logits;
   P.status = f->status; P.trace = (f->shape.flags & (FLEET_FLAG_TRACE | FLEET_FLAG_TIMING)) ? f->trace : nullptr; P.trace_cap = TRACE_CAP;
@@ -354,12 +381,32 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
   if ((rc = upload(&f->x, nullptr, mb * H * 4))) return rc;
   // bf16 activations: feature dimension padded to whole 256-wide chunks (the MFMA kernels
   // store them chunk-tiled)
+  // (the MFMA kernels store them as operand blocks of 16 rows)
   auto pad256 = [](size_t k) { return (k + 255) / 256 * 256; };
-  if ((rc = upload((char**)&f->n, nullptr, mb * pad256(H) * 2))) return rc;
+  const size_t mb16 = (mb + 15) / 16 * 16;
+  if ((rc = upload((char**)&f->n, nullptr, mb16 * pad256(H) * 2))) return rc;
   if ((rc = upload(&f->qkv, nullptr, mb * NQKV * 4))) return rc;
-  if ((rc = upload((char**)&f->att, nullptr, mb * pad256(QD) * 2))) return rc;
-  if ((rc = upload((char**)&f->h, nullptr, mb * pad256(F) * 2))) return rc;
+  if ((rc = upload((char**)&f->att, nullptr, mb16 * pad256(QD) * 2))) return rc;
+  if ((rc = upload((char**)&f->h, nullptr, mb16 * pad256(F) * 2))) return rc;
   if ((rc = upload(&f->part, nullptr, mb * shape->n_kv_heads * 32 * grp * dev::PART_STRIDE * 4))) return rc;
+  if (shape->max_batch > fma_max_batch()) {
+    f->pk_qkv.assign(L, nullptr); f->pk_o.assign(L, nullptr); f->pk_gu.assign(L, nullptr); f->pk_down.assign(L, nullptr);
+    for (int l = 0; l < L; ++l) {
+      if ((rc = pack_matrix(&f->pk_qkv[l], f->wqkv[l], (int)NQKV, (int)H, true))) return rc;
+      if ((rc = pack_matrix(&f->pk_o[l], f->wo[l], (int)H, (int)QD, true))) return rc;
+      if ((rc = pack_matrix(&f->pk_gu[l], f->wgu[l], (int)(2 * F), (int)H, true))) return rc;
+      if ((rc = pack_matrix(&f->pk_down[l], f->wdown[l], (int)H, (int)F, true))) return rc;
+    }
+    if (shape->vocab > 0 && (rc = pack_matrix(&f->pk_lm, f->lm_head, shape->vocab, (int)H, true))) return rc;
+    HIP_TRY(hipDeviceSynchronize());
+  }
+  // partial sums of split-K GEMM tiles (MFMA kernels): up to 8 k-slices of the widest output a
+  // split plan can have, batch rows padded to the 64 one m-tile can hold
+  if (shape->max_batch > fma_max_batch()) {
+    size_t nmax = std::max({NQKV, H, 2 * F});
+    if (shape->vocab > 0 && (size_t)shape->vocab / 16 * 4 <= (size_t)GEMM_TILE_COUNTERS) nmax = std::max(nmax, (size_t)shape->vocab);
+    if ((rc = upload(&f->gpart, nullptr, 8 * 64 * nmax * 4))) return rc;
+  }
   if ((rc = upload(&f->status, nullptr, dev::ST_WORDS * 4))) return rc;
   HIP_TRY(hipMemset(f->status, 0, dev::ST_WORDS * 4));
   if (shape->flags & (FLEET_FLAG_TRACE | FLEET_FLAG_TIMING))
@@ -384,8 +431,11 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
 int fleet_destroy(fleet_t* f) {
   if (!f) return FLEET_OK;
   (void)hipDeviceSynchronize();
-  for (void* p : {(void*)f->x, f->n, (void*)f->qkv, f->att, f->h, (void*)f->part, (void*)f->rope, (void*)f->status, (void*)f->trace})
+  for (void* p : {(void*)f->x, f->n, (void*)f->qkv, f->att, f->h, (void*)f->part, (void*)f->gpart, (void*)f->rope, (void*)f->status, (void*)f->trace})
     if (p) (void)hipFree(p);
+  for (auto* v : {&f->pk_qkv, &f->pk_o, &f->pk_gu, &f->pk_down})
+    for (void* p : *v) if (p) (void)hipFree(p);
+  if (f->pk_lm) (void)hipFree(f->pk_lm);
   delete f;
   return FLEET_OK;
 }
@@ -498,13 +548,27 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const
   if (rc) return rc;
   DevGraph dg;
   dg.g = build_gemm_graph(B, K, N, sched_mode, tile_m, flags, reps, n_copies, info.n_xcd, info.n_cu);
-  if ((rc = upload_graph(&dg, nullptr, w_copies, info.n_xcd))) return rc;
+  // the MFMA kernels read operand blocks: pack the caller's matrices into private copies
+  const bool mfma = dg.g.header[H_PATH] == P_MFMA;
+  std::vector<void*> packed;
+  void* xp = nullptr;
+  auto free_packed = [&]() { for (void* p : packed) if (p) (void)hipFree(p); if (xp) (void)hipFree(xp); };
+  if (mfma) {
+    packed.assign(n_copies, nullptr);
+    for (int i = 0; i < n_copies; ++i)
+      if ((rc = pack_matrix(&packed[i], w_copies[i], N, K, true))) { free_packed(); return rc; }
+    if ((rc = pack_matrix(&xp, x, B, K, false))) { free_packed(); return rc; }
+    if (hipDeviceSynchronize() != hipSuccess) { free_packed(); return FLEET_EHIP; }
+  }
+  if ((rc = upload_graph(&dg, nullptr, mfma ? (const void* const*)packed.data() : w_copies, info.n_xcd))) { free_packed(); return rc; }
   int32_t* status = nullptr;
-  if ((rc = upload(&status, nullptr, dev::ST_WORDS * 4))) return rc;
+  if ((rc = upload(&status, nullptr, dev::ST_WORDS * 4))) { free_packed(); return rc; }
+  float* gpart = nullptr;   // partial sums of split-K tiles
+  if ((rc = upload(&gpart, nullptr, (size_t)8 * 64 * N * 4))) { (void)hipFree(status); free_packed(); return rc; }
   dev::Params P;
   memset(&P, 0, sizeof(P));
   fill_graph_params(P, &dg);
-  P.buf[BUF_GEMM_X] = (void*)x; P.buf[BUF_GEMM_Y] = y;
+  P.buf[BUF_GEMM_X] = mfma ? xp : (void*)x; P.buf[BUF_GEMM_Y] = y; P.buf[BUF_GPART] = gpart;
   P.status = status; P.timeout_ticks = timeout_ticks_from_env(); P.n_xcd = info.n_xcd; P.flags = flags;
   P.batch = B; P.hidden = K;
   for (int xc = 0; xc < info.n_xcd; ++xc) { P.q_begin[xc] = dg.g.marks[(size_t)xc * 3 + 0]; P.q_end[xc] = dg.g.marks[(size_t)xc * 3 + 2]; }
@@ -527,6 +591,8 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
   (void)hipFree(status);
+  (void)hipFree(gpart);
+  free_packed();
   if (he != hipSuccess) { g_last_hip = (int)he; return FLEET_EHIP; }
   return code[dev::ST_CODE];
 }

@@ -1,5 +1,6 @@
 // Host-side task-graph builder (see graph.hpp for the layout and citations).
 #include "graph.hpp"
+#include <cstdlib>
 
 #include <algorithm>
 #include <cstring>
@@ -80,16 +81,21 @@ struct Builder {
     const int U = o[O_N_UNITS], mt = o[O_M_TILES];
     int ev;
     if (sched == FLEET_SCHED_UNAWARE) {
-      int cu_units = std::max(1, U / std::max(1, n_workers));
+      // FMA path: as many units per CU-task as spread U over the workers once;
+      // MFMA path: the operator's tile plan (units per tile, k-slices)
+      const bool mfma = o[O_PATH] == P_MFMA;
+      const int cu_units = mfma ? std::max(1, (o[O_AUX2] >> 12) & 15) : std::max(1, U / std::max(1, n_workers));
+      const int ksn = mfma ? std::max(1, (o[O_AUX2] >> 16) & 15) : 1;
       int ng = (U + cu_units - 1) / cu_units;
-      ev = add_event(ng * mt, EV_DIRECT, 0, ng * mt);
+      ev = add_event(ng * mt * ksn, EV_DIRECT, 0, ng * mt * ksn);
       int first = g.n_tasks();
       for (int m = 0; m < mt; ++m)
-        for (int gi = 0; gi < ng; ++gi) {
-          int u0 = gi * cu_units, cnt = std::min(cu_units, U - u0);
-          add_task(op, S_CU, -1, u0, cnt, m, 0, wait_ev, ev);
-        }
-      for (int x = 0; x < n_xcd; ++x) push_q(x, first, ng * mt, D_DEV_RR);
+        for (int ks = 0; ks < ksn; ++ks)
+          for (int gi = 0; gi < ng; ++gi) {
+            int u0 = gi * cu_units, cnt = std::min(cu_units, U - u0);
+            add_task(op, S_CU, -1, u0, cnt, m, ks, wait_ev, ev);
+          }
+      for (int x = 0; x < n_xcd; ++x) push_q(x, first, ng * mt * ksn, D_DEV_RR);
     } else {
       int mask = 0, nx = 0;
       for (int x = 0; x < n_xcd; ++x) {
@@ -147,8 +153,35 @@ std::vector<int32_t> Graph::serialize() const {
   return out;
 }
 
+// Tile plan of an MFMA GEMM operator: G units per tile and KS k-slices, chosen so that the
+// tiles of one XCD's unit slice keep its workers equally busy and the tiles are tall:
+// minimise ceil(tiles / workers) * (G + 2) / KS -- a tile of G units costs about G + 2,
+// because the weight bytes a worker keeps in flight grow with G and the activations are
+// read once per tile -- then prefer more units per tile, then fewer slices.
+MfmaPlan plan_mfma(int n_units, int K, int nb, int mt_blocks, int m_tiles, int n_xcd, int n_workers) {
+  const int gmax = std::max(1, ((mt_blocks >= 4 || nb == 2) ? 6 : 8) / nb);
+  const int ux = (n_units + n_xcd - 1) / std::max(1, n_xcd), wpx = std::max(1, n_workers / std::max(1, n_xcd));
+  MfmaPlan best{1, 1};
+  long best_cost = -1;
+  for (int G = 1; G <= std::min(gmax, std::max(1, ux)); ++G)
+    for (int KS = 1; KS <= 8; KS *= 2) {
+      if (KS > 1 && (K % (KS * 256) != 0 || (long)n_units * m_tiles > GEMM_TILE_COUNTERS)) continue;
+      const long tiles = (long)((ux + G - 1) / G) * KS * m_tiles;
+      const long cost = ((tiles + wpx - 1) / wpx) * (G + 2) * (8 / KS);
+      if (best_cost < 0 || cost < best_cost || (cost == best_cost && (G > best.G || (G == best.G && KS < best.KS)))) {
+        best_cost = cost; best.G = G; best.KS = KS;
+      }
+    }
+  return best;
+}
+
+static int fma_max() { const char* e = getenv("FLEET_FMA_MAX_BATCH"); return e ? atoi(e) : 8; }
+int fma_max_batch() { return fma_max(); }
+
+int mfma_blocks(int tile_m) { return tile_m <= 16 ? 1 : tile_m <= 32 ? 2 : 4; }
+
 int resolve_tile_m(int batch, int tile_m) {
-  if (batch <= 8) return batch;  // FMA GEMV path: one tile holds the whole batch
+  if (batch <= fma_max()) return batch;  // FMA GEMV path: one tile holds the whole batch
   if (tile_m == 0) return ((batch + 15) / 16) * 16;
   return tile_m;
 }
@@ -179,11 +212,18 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   Builder b(n_xcd, n_workers, s.sched_mode, batch);
   const int H = s.hidden, hd = s.head_dim, nq = s.n_q_heads, nkv = s.n_kv_heads, F = s.ffn;
   const int QD = nq * hd, NQKV = (nq + 2 * nkv) * hd;
-  const Path path = batch <= 8 ? P_FMA : P_MFMA;
+  const Path path = batch <= fma_max() ? P_FMA : P_MFMA;
   const int ur = path == P_FMA ? 8 : 16;
   const int tm = resolve_tile_m(batch, s.tile_m);
   const int mt = (batch + tm - 1) / tm;
   const int S = attention_splits(batch, nkv, n_workers, s.max_seq);
+
+  // MFMA operators carry their tile plan in aux2: bits 12..15 units per tile, 16..19 k-slices
+  auto plan_bits = [&](int n_units, int K, int nb) {
+    if (path != P_MFMA) return 0;
+    const MfmaPlan pl = plan_mfma(n_units, K, nb, mfma_blocks(tm), mt, n_xcd, n_workers);
+    return (pl.G << 12) | (pl.KS << 16);
+  };
 
   auto row_key = [](int i) { return i; };
   auto row_arg = [](int i, int* a) { a[0] = i; a[1] = a[2] = a[3] = 0; };
@@ -209,12 +249,12 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
     int op_qkv;
     if (fuse_norm) {
       op_qkv = b.add_op(B_GEMM, l, E_STORE_F32, path, H, NQKV, ur, NQKV / ur, mt, tm, BUF_X, BUF_QKV, 0, W_QKV,
-                        W_LN1 | (X_LDS_NORM << 8) | PRE2);
+                        W_LN1 | (X_LDS_NORM << 8) | PRE2);   // FMA path only
     } else {
       int op_n1 = b.add_op(B_RMSNORM, l, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N, 0, W_LN1);
       ev = b.cu_stage(op_n1, batch, ev, row_key, row_arg);
       op_qkv = b.add_op(B_GEMM, l, E_STORE_F32, path, H, NQKV, ur, NQKV / ur, mt, tm, BUF_N, BUF_QKV, 0, W_QKV,
-                        (xmode(H) << 8) | PRE2);
+                        (xmode(H) << 8) | PRE2 | plan_bits(NQKV / ur, H, 1));
     }
     ev = b.gemm_stage(op_qkv, ev);
 
@@ -224,7 +264,8 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
                     [S](int i) { return i / S; },
                     [S, nkv](int i, int* a) { int p = i / S; a[0] = p / nkv; a[1] = p % nkv; a[2] = i % S; a[3] = S; });
 
-    int op_o = b.add_op(B_GEMM, l, E_RESID_F32, path, QD, H, ur, H / ur, mt, tm, BUF_ATT, BUF_X, 0, W_O, (xmode(QD) << 8) | PRE2);
+    int op_o = b.add_op(B_GEMM, l, E_RESID_F32, path, QD, H, ur, H / ur, mt, tm, BUF_ATT, BUF_X, 0, W_O,
+                      (xmode(QD) << 8) | PRE2 | plan_bits(H / ur, QD, 1));
     ev = b.gemm_stage(op_o, ev);
 
     // gate | up rows of one concatenated matrix; a unit is ur gate rows plus the
@@ -236,11 +277,13 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
     } else {
       int op_n2 = b.add_op(B_RMSNORM, l, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N, 0, W_LN2);
       ev = b.cu_stage(op_n2, batch, ev, row_key, row_arg);
-      op_gu = b.add_op(B_GEMM, l, E_SWIGLU_BF16, path, H, F, ur, F / ur, mt, tm, BUF_N, BUF_H, F, W_GU, (xmode(H) << 8) | PRE2);
+      op_gu = b.add_op(B_GEMM, l, E_SWIGLU_BF16, path, H, F, ur, F / ur, mt, tm, BUF_N, BUF_H, F, W_GU,
+                       (xmode(H) << 8) | PRE2 | plan_bits(F / ur, H, 2));
     }
     ev = b.gemm_stage(op_gu, ev);
 
-    int op_dn = b.add_op(B_GEMM, l, E_RESID_F32, path, F, H, ur, H / ur, mt, tm, BUF_H, BUF_X, 0, W_DOWN, (xmode(F) << 8) | PRE2);
+    int op_dn = b.add_op(B_GEMM, l, E_RESID_F32, path, F, H, ur, H / ur, mt, tm, BUF_H, BUF_X, 0, W_DOWN,
+                      (xmode(F) << 8) | PRE2 | plan_bits(H / ur, F, 1));
     ev = b.gemm_stage(op_dn, ev);
     b.g.xready.push_back(ev);
   }
@@ -252,7 +295,7 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   ev = b.cu_stage(op_fin, batch, ev, row_key, row_arg);
   if (s.vocab > 0) {
     int op_lm = b.add_op(B_GEMM, -1, E_STORE_F32, path, H, s.vocab, ur, s.vocab / ur, mt, tm, BUF_N,
-                         BUF_LOGITS, 0, W_LM, (xmode(H) << 8) | PRE2);
+                         BUF_LOGITS, 0, W_LM, (xmode(H) << 8) | PRE2 | plan_bits(s.vocab / ur, H, 1));
     ev = b.gemm_stage(op_lm, ev);
   }
   b.mark_all();
@@ -262,20 +305,28 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
 Graph build_gemm_graph(int B, int K, int N, int sched_mode, int tile_m, int flags, int reps,
                        int n_copies, int n_xcd, int n_workers) {
   Builder b(n_xcd, n_workers, sched_mode, B);
-  const Path path = B <= 8 ? P_FMA : P_MFMA;
+  const Path path = B <= fma_max() ? P_FMA : P_MFMA;
   const int ur = path == P_FMA ? 8 : 16;
   const int tm = resolve_tile_m(B, tile_m);
   const int mt = (B + tm - 1) / tm;
   int ev = -1;
   b.mark_all();
   b.mark_all();
+  // Repetitions are independent unless FLEET_FLAG_CHAINED is set.  Split-K tiles count
+  // their arrivals in one of two counter sets (bit 20 of aux2), so a repetition of such a
+  // plan waits for the one before the previous: at most two are in flight.
+  MfmaPlan pl{1, 1};
+  if (path == P_MFMA) pl = plan_mfma(N / ur, K, 1, mfma_blocks(tm), mt, n_xcd, n_workers);
+  std::vector<int> evs;
   for (int r = 0; r < reps; ++r) {
     const int xm = path == P_FMA && (int64_t)B * K * 2 <= GEMV_LDS_X_BYTES && !(flags & FLEET_FLAG_SEPARATE_NORM)
                        ? X_LDS_COPY : X_GLOBAL;
+    const int bits = path == P_MFMA ? (pl.G << 12) | (pl.KS << 16) | ((r & 1) << 20) : 0;
     int op = b.add_op(B_GEMM, r % std::max(1, n_copies), E_STORE_F32, path, K, N, ur, N / ur, mt, tm,
-                      BUF_GEMM_X, BUF_GEMM_Y, 0, W_GEMM_COPY, (xm << 8) | (3 << 10));
-    int e = b.gemm_stage(op, (flags & 8) ? ev : -1);
-    ev = e;
+                      BUF_GEMM_X, BUF_GEMM_Y, 0, W_GEMM_COPY, (xm << 8) | (3 << 10) | bits);
+    int wait = (flags & FLEET_FLAG_CHAINED) ? ev : (pl.KS > 1 && r >= 2) ? evs[r - 2] : -1;
+    ev = b.gemm_stage(op, wait);
+    evs.push_back(ev);
   }
   b.mark_all();
   b.g.xready.push_back(-1);

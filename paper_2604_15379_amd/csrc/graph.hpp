@@ -45,7 +45,7 @@ enum EventKind { EV_DIRECT = 0, EV_TWO_LEVEL = 1 };
 // activation / caller buffers, resolved to pointers per step
 enum Buf {
   BUF_NONE = 0, BUF_X, BUF_N, BUF_QKV, BUF_ATT, BUF_H, BUF_PART, BUF_HIDDEN_IN, BUF_TOKENS,
-  BUF_KC, BUF_VC, BUF_POS, BUF_HIDDEN_OUT, BUF_LOGITS, BUF_GEMM_X, BUF_GEMM_Y, N_BUF
+  BUF_KC, BUF_VC, BUF_POS, BUF_HIDDEN_OUT, BUF_LOGITS, BUF_GEMM_X, BUF_GEMM_Y, BUF_GPART, N_BUF
 };
 
 // which caller weight an op reads (resolved with the op's layer)
@@ -60,12 +60,14 @@ enum {
 };
 // O_AUX2 of a GEMM op: low byte = WKind of the fused RMSNorm gain (W_NONE if none),
 // bits 8..9 = activation mode of the FMA path (XMode), bits 10..11 = weight blocks the FMA
-// path requests before its dependency wait (0..3)
+// path requests before its dependency wait (0..3); MFMA path: bits 12..15 = units per tile,
+// bits 16..19 = k-slices of the split-K plan (1 = no split), bit 20 = counter set of the
+// split-K arrival counters (isolated GEMM repetitions alternate)
 enum XMode { X_GLOBAL = 0, X_LDS_COPY = 1, X_LDS_NORM = 2 };
 constexpr int GEMV_LDS_X_BYTES = 96 * 1024;   // LDS the FMA path may fill with activations
 // task word indices.  A0..A3 by body:
 //   GEMM chiplet-task : A0 first unit, A1 unit count            (tiles = units x m_tiles)
-//   GEMM CU-task      : A0 first unit, A1 unit count, A2 m-tile
+//   GEMM CU-task      : A0 first unit, A1 unit count, A2 m-tile, A3 k-slice
 //   ATTN              : A0 batch row, A1 kv head, A2 split, A3 n_splits
 //   INGEST/RMSNORM/FINAL : A0 batch row
 enum { T_OP = 0, T_SCOPE, T_XCD, T_A0, T_A1, T_A2, T_A3, T_WAIT_EVENT, T_SIGNAL_EVENT, T_STAGE };
@@ -84,6 +86,15 @@ struct Graph {
   std::vector<int32_t> serialize() const;
 };
 
+// Tile plan of an MFMA GEMM operator (units per tile, k-slices); a split-K plan needs one
+// arrival counter per (first unit of a tile, m-tile), GEMM_TILE_COUNTERS at most
+constexpr int GEMM_TILE_COUNTERS = 4096;
+struct MfmaPlan { int G, KS; };
+MfmaPlan plan_mfma(int n_units, int K, int nb, int mt_blocks, int m_tiles, int n_xcd, int n_workers);
+// 16-row blocks of batch rows the MFMA kernel for tile height tile_m accumulates (1, 2 or 4)
+int mfma_blocks(int tile_m);
+// largest batch that runs the FMA GEMV kernels (larger batches run the MFMA kernels)
+int fma_max_batch();
 // tile_m actually used for `batch` (0 = whole batch rounded up to 16; FMA path: batch)
 int resolve_tile_m(int batch, int tile_m);
 // KV splits per (sequence, kv head)

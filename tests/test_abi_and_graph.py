@@ -122,19 +122,41 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
         stage[0] += 1
         return ev
 
+    def plan(U, K, nb):
+        """MFMA tile plan: units per tile G and k-slices KS keeping one XCD's workers equally
+        busy with tall tiles (a tile of G units is charged G + 2); ties go to more units per
+        tile, then to fewer slices.  Packed into aux2."""
+        if fma:
+            return 0
+        blocks = 1 if tm <= 16 else 2 if tm <= 32 else 4
+        gmax = max(1, (6 if blocks >= 4 or nb == 2 else 8) // nb)
+        ux, wpx = -(-U // n_xcd), max(1, n_workers // n_xcd)
+        best = None
+        for G in range(1, min(gmax, max(1, ux)) + 1):
+            for KS in (1, 2, 4, 8):
+                if KS > 1 and (K % (KS * 256) or U * mt > 4096):
+                    continue
+                tiles = -(-ux // G) * KS * mt
+                cost = -(-tiles // wpx) * (G + 2) * (8 // KS)
+                if best is None or (cost, -G, KS) < best[0]:
+                    best = ((cost, -G, KS), G, KS)
+        return best[1] << 12 | best[2] << 16
+
     def gemm_stage(o, wait):
         U, m_tiles = ops[o][7], ops[o][8]
         ev = len(events)
         if sched == 1:
-            cu = max(1, U // n_workers)
+            cu = max(1, U // n_workers) if fma else max(1, ops[o][15] >> 12 & 15)
+            ksn = 1 if fma else max(1, ops[o][15] >> 16 & 15)
             ng = -(-U // cu)
-            events.append([ng * m_tiles, 0, 0, ng * m_tiles])
+            events.append([ng * m_tiles * ksn, 0, 0, ng * m_tiles * ksn])
             first = len(tasks)
             for m in range(m_tiles):
-                for g in range(ng):
-                    task(o, 1, -1, [g * cu, min(cu, U - g * cu), m, 0], wait, ev)
+                for ks in range(ksn):
+                    for g in range(ng):
+                        task(o, 1, -1, [g * cu, min(cu, U - g * cu), m, ks], wait, ev)
             for x in range(n_xcd):
-                queues[x].append([first, ng * m_tiles, 2, stage[0]])
+                queues[x].append([first, ng * m_tiles * ksn, 2, stage[0]])
         else:
             bounds = [U * x // n_xcd for x in range(n_xcd + 1)]
             owners = [x for x in range(n_xcd) if bounds[x + 1] > bounds[x]]
@@ -170,26 +192,30 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
                        WK["LN1"] | 2 << 8 | PRE)
         else:
             ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN1"]), rows, ev)
-            o_qkv = op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["N"], BUF["QKV"], 0, WK["QKV"], xm(H))
+            o_qkv = op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["N"], BUF["QKV"], 0, WK["QKV"],
+                       xm(H) | plan(NQKV // ur, H, 1))
         ev = gemm_stage(o_qkv, ev)
         att_items = [(p, [p // nkv, p % nkv, s, S]) for p in range(batch * nkv) for s in range(S)]
         ev = cu_stage(op(ATTN, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["QKV"], BUF["ATT"], S, WK["NONE"]), att_items, ev)
-        ev = gemm_stage(op(GEMM, l, 1, path, QD, H, ur, H // ur, mt, tm, BUF["ATT"], BUF["X"], 0, WK["O"], xm(QD)), ev)
+        ev = gemm_stage(op(GEMM, l, 1, path, QD, H, ur, H // ur, mt, tm, BUF["ATT"], BUF["X"], 0, WK["O"],
+                           xm(QD) | plan(H // ur, QD, 1)), ev)
         if fuse:
             o_gu = op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["X"], BUF["H"], Fd, WK["GU"],
                       WK["LN2"] | 2 << 8 | PRE)
         else:
             ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN2"]), rows, ev)
-            o_gu = op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["N"], BUF["H"], Fd, WK["GU"], xm(H))
+            o_gu = op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["N"], BUF["H"], Fd, WK["GU"],
+                      xm(H) | plan(Fd // ur, H, 2))
         ev = gemm_stage(o_gu, ev)
-        ev = gemm_stage(op(GEMM, l, 1, path, Fd, H, ur, H // ur, mt, tm, BUF["H"], BUF["X"], 0, WK["DOWN"], xm(Fd)), ev)
+        ev = gemm_stage(op(GEMM, l, 1, path, Fd, H, ur, H // ur, mt, tm, BUF["H"], BUF["X"], 0, WK["DOWN"],
+                           xm(Fd) | plan(H // ur, Fd, 1)), ev)
         xready.append(ev)
     mark()
     ev = cu_stage(op(FINAL, -1, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 1 if sh.vocab else 0, WK["FINAL"]),
                   rows, ev)
     if sh.vocab:
         gemm_stage(op(GEMM, -1, 0, path, H, sh.vocab, ur, sh.vocab // ur, mt, tm, BUF["N"], BUF["LOGITS"], 0,
-                      WK["LM"], xm(H)), ev)
+                      WK["LM"], xm(H) | plan(sh.vocab // ur, H, 1)), ev)
     mark()
     qoff = np.cumsum([0] + [len(q) for q in queues])
     return dict(ops=np.array(ops, np.int32), tasks=np.array(tasks, np.int32),
@@ -260,17 +286,21 @@ def test_graph_invariants(batch, sched):
     for x in range(8):
         st = g["qents"][g["qoff"][x]:g["qoff"][x + 1], 3]
         assert (np.diff(st) > 0).all()
-    # GEMM device-tasks tile the output exactly once
+    # GEMM device-tasks tile the output exactly once per k-slice of the operator's plan
     for o, op in enumerate(ops):
         if op[0] != GEMM:
             continue
-        cover = np.zeros((op[7], op[8]), int)
+        ksn = max(1, op[15] >> 16 & 15) if op[3] == 1 else 1
+        cover = np.zeros((op[7], op[8], ksn), int)
         for t in tasks[tasks[:, 0] == o]:
             if t[1] == 2:
-                cover[t[3]:t[3] + t[4], :] += 1
+                cover[t[3]:t[3] + t[4], :, :] += 1      # a chiplet-task walks all its tiles
             else:
-                cover[t[3]:t[3] + t[4], t[5]] += 1
+                cover[t[3]:t[3] + t[4], t[5], t[6]] += 1
+                assert op[3] == 0 or t[4] <= max(1, op[15] >> 12 & 15)
         assert (cover == 1).all()
+        if ksn > 1:
+            assert op[4] % (ksn * 256) == 0 and op[7] * op[8] <= 4096
         assert op[8] == -(-batch // op[9]) and op[5] == op[6] * op[7]
 
 
