@@ -254,6 +254,13 @@ int upload_graph(DevGraph* dg, const fleet* f, const void* const* gemm_copies, i
     memcpy(d + dev::FAT_W2, &w2[tw[T_OP]], sizeof(void*));
     d[dev::FAT_ID] = t;
   }
+  // CU-tasks dealt inside one XCD: how many of them signal the task's event from that XCD
+  for (int x = 0; x < n_xcd; ++x)
+    for (int qi = g.qoff[x]; qi < g.qoff[x + 1]; ++qi) {
+      const int32_t* e = &g.qents[(size_t)qi * QENT_WORDS];
+      if (e[Q_DIST] != D_XCD_RR) continue;
+      for (int t = e[Q_FIRST]; t < e[Q_FIRST] + e[Q_COUNT]; ++t) fat[(size_t)t * dev::FAT_WORDS + dev::FAT_GROUP] = e[Q_COUNT];
+    }
   if ((rc = upload(&dg->fat, fat.data(), fat.size() * 4))) return rc;
   // G[e], L[x][e], then one arrival counter per (sequence, kv head) for the split-KV merge
   // and one relay word per worker on its own cache line

@@ -47,9 +47,21 @@ struct Builder {
   // A stage of CU-tasks, one per item; item i belongs to XCD key(i) % n_xcd in
   // the cooperative schedule (round-robin inside the XCD), to any worker in the
   // chiplet-unaware one.  args(i) fills A0..A3.  Returns the signalled event.
+  // Few tasks per XCD (at most min_per_xcd on average): each signals the device counter itself
+  // (one atomic less on the path).  More: two-level, one release and one device-level signal
+  // per XCD.
   template <class KeyF, class ArgF>
-  int cu_stage(int op, int n_items, int wait_ev, KeyF key, ArgF args) {
-    int ev = add_event(n_items, EV_DIRECT, 0, n_items);
+  int cu_stage(int op, int n_items, int wait_ev, KeyF key, ArgF args, int min_per_xcd = 1) {
+    int ev;
+    const bool two_level = sched != FLEET_SCHED_UNAWARE && n_items > min_per_xcd * n_xcd;
+    if (!two_level) {
+      ev = add_event(n_items, EV_DIRECT, 0, n_items);
+    } else {   // one device-level signal per XCD that runs some of the tasks
+      int mask = 0, nx = 0;
+      for (int i = 0; i < n_items; ++i) mask |= 1 << (key(i) % n_xcd);
+      for (int x = 0; x < n_xcd; ++x) nx += (mask >> x) & 1;
+      ev = add_event(nx, EV_TWO_LEVEL_CU, mask, n_items);
+    }
     if (sched == FLEET_SCHED_UNAWARE) {
       int first = g.n_tasks();
       for (int i = 0; i < n_items; ++i) {
@@ -175,7 +187,14 @@ MfmaPlan plan_mfma(int n_units, int K, int nb, int mt_blocks, int m_tiles, int n
   return best;
 }
 
-static int fma_max() { const char* e = getenv("FLEET_FMA_MAX_BATCH"); return e ? atoi(e) : 8; }
+// Largest batch that runs the FMA GEMV kernels.  Measured on MI355X the MFMA kernels win from
+// batch 5 on (batch 8: 4.7 ms against 6.4 ms per step), so the default is 4; the environment
+// variable FLEET_FMA_MAX_BATCH (0..8) moves the switch, e.g. to 8 for FMA at batch 5-8.
+static int fma_max() {
+  const char* e = getenv("FLEET_FMA_MAX_BATCH");
+  if (!e) return 4;
+  return std::min(8, std::max(0, atoi(e)));
+}
 int fma_max_batch() { return fma_max(); }
 
 int mfma_blocks(int tile_m) { return tile_m <= 16 ? 1 : tile_m <= 32 ? 2 : 4; }
@@ -262,7 +281,10 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
     int op_att = b.add_op(B_ATTN, l, E_STORE_F32, P_FMA, hd, QD, 0, 0, 1, batch, BUF_QKV, BUF_ATT, S, W_NONE);
     ev = b.cu_stage(op_att, batch * nkv * S, ev,
                     [S](int i) { return i / S; },
-                    [S, nkv](int i, int* a) { int p = i / S; a[0] = p / nkv; a[1] = p % nkv; a[2] = i % S; a[3] = S; });
+                    [S, nkv](int i, int* a) { int p = i / S; a[0] = p / nkv; a[1] = p % nkv; a[2] = i % S; a[3] = S; },
+                    // splits that do not merge publish nothing and skip the release when they
+                    // signal directly: two-level pays only with many tasks per XCD
+                    ATTN_TWO_LEVEL_MIN_PER_XCD);
 
     int op_o = b.add_op(B_GEMM, l, E_RESID_F32, path, QD, H, ur, H / ur, mt, tm, BUF_ATT, BUF_X, 0, W_O,
                       (xmode(QD) << 8) | PRE2 | plan_bits(H / ur, QD, 1));

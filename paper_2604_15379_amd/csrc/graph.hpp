@@ -40,7 +40,12 @@ enum Epi { E_STORE_F32 = 0, E_RESID_F32 = 1, E_SWIGLU_BF16 = 2 };
 enum Path { P_FMA = 0, P_MFMA = 1 };
 enum Scope { S_WAVE = 0, S_CU = 1, S_CHIPLET = 2 };
 enum Dist { D_CHIPLET = 0, D_XCD_RR = 1, D_DEV_RR = 2 };
-enum EventKind { EV_DIRECT = 0, EV_TWO_LEVEL = 1 };
+// EV_TWO_LEVEL: signalled by the workers of chiplet-tasks; EV_TWO_LEVEL_CU: by CU-tasks
+// grouped per XCD (cooperative schedule); EV_DIRECT: by CU-tasks running anywhere
+enum EventKind { EV_DIRECT = 0, EV_TWO_LEVEL = 1, EV_TWO_LEVEL_CU = 2 };
+// a stage of CU-tasks signals two-level when it has more than one task per XCD on average
+// (attention stages: more than this many)
+constexpr int ATTN_TWO_LEVEL_MIN_PER_XCD = 8;
 
 // activation / caller buffers, resolved to pointers per step
 enum Buf {
@@ -72,7 +77,7 @@ constexpr int GEMV_LDS_X_BYTES = 96 * 1024;   // LDS the FMA path may fill with 
 //   INGEST/RMSNORM/FINAL : A0 batch row
 enum { T_OP = 0, T_SCOPE, T_XCD, T_A0, T_A1, T_A2, T_A3, T_WAIT_EVENT, T_SIGNAL_EVENT, T_STAGE };
 // event word indices: threshold counts device-level signals (XCDs for a
-// two-level event, tasks for a direct one)
+// two-level event, tasks for a direct one); n_tasks counts the signalling tasks
 enum { E_THRESHOLD = 0, E_KIND, E_XCD_MASK, E_N_TASKS };
 // queue entry word indices
 enum { Q_FIRST = 0, Q_COUNT, Q_DIST, Q_STAGE };

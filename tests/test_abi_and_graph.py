@@ -81,10 +81,13 @@ INGEST, RMSNORM, GEMM, ATTN, FINAL = 0, 1, 2, 3, 5
 LDS_X_BYTES = 96 * 1024      # activations the FMA path may keep in LDS
 
 
+FMA_MAX = 4   # largest batch on the FMA GEMV path (FLEET_FMA_MAX_BATCH unset)
+
+
 def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0):
     """Independent derivation of the serialized graph (same word layout)."""
     H, hd, nq, nkv, Fd = sh.hidden, sh.head_dim, sh.n_q_heads, sh.n_kv_heads, sh.ffn
-    fma = batch <= 8
+    fma = batch <= FMA_MAX
     ur = 8 if fma else 16
     tm = batch if fma else (tile_m or -(-batch // 16) * 16)
     mt = -(-batch // tm)
@@ -103,9 +106,13 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
         tasks.append([o, scope, xcd, *a, wait, sig, stage[0]] + [0] * 6)
         return len(tasks) - 1
 
-    def cu_stage(o, items, wait):
+    def cu_stage(o, items, wait, min_per_xcd=1):
         ev = len(events)
-        events.append([len(items), 0, 0, len(items)])
+        if sched == 1 or len(items) <= min_per_xcd * n_xcd:   # tasks run anywhere, or few per XCD: every
+            events.append([len(items), 0, 0, len(items)])   # task signals the device counter
+        else:               # grouped per XCD: one device-level signal per XCD with tasks (kind 2)
+            owners = sorted({key % n_xcd for key, a in items})
+            events.append([len(owners), 2, sum(1 << x for x in owners), len(items)])
         if sched == 1:
             first = len(tasks)
             for key, a in items:
@@ -176,7 +183,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
     mark()
     ev = cu_stage(op(INGEST, -1, 0, 0, H, H, 0, 0, 1, batch, BUF["HIDDEN_IN"], BUF["X"], 0, WK["EMBED"]), rows, -1)
     xready.append(ev)
-    # batch <= 8: RMSNorm fused into the consuming GEMV (activation mode 2, gain kind in the
+    # FMA path: RMSNorm fused into the consuming GEMV (activation mode 2, gain kind in the
     # low byte of aux2); activations that fit LDS are copied there (mode 1), else mode 0
     fuse = fma and not (flags & 4) and batch * H * 2 <= LDS_X_BYTES
 
@@ -196,7 +203,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
                        xm(H) | plan(NQKV // ur, H, 1))
         ev = gemm_stage(o_qkv, ev)
         att_items = [(p, [p // nkv, p % nkv, s, S]) for p in range(batch * nkv) for s in range(S)]
-        ev = cu_stage(op(ATTN, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["QKV"], BUF["ATT"], S, WK["NONE"]), att_items, ev)
+        ev = cu_stage(op(ATTN, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["QKV"], BUF["ATT"], S, WK["NONE"]), att_items, ev, 8)
         ev = gemm_stage(op(GEMM, l, 1, path, QD, H, ur, H // ur, mt, tm, BUF["ATT"], BUF["X"], 0, WK["O"],
                            xm(QD) | plan(H // ur, QD, 1)), ev)
         if fuse:
@@ -262,10 +269,13 @@ def test_graph_invariants(batch, sched):
     prod = _producers(g)
     # thresholds: one device-level signal per chiplet for two-level events, per task otherwise
     for e, ev in enumerate(events):
-        assert ev[0] == len(prod[e]) == ev[3]
-        if ev[1] == 1:
+        assert ev[3] == len(prod[e])
+        if ev[1] == 0:
+            assert ev[0] == len(prod[e])
+        else:
             assert bin(int(ev[2])).count("1") == ev[0]
-            assert sorted(int(tasks[t][2]) for t in prod[e]) == [x for x in range(8) if ev[2] >> x & 1]
+            assert sorted({int(tasks[t][2]) for t in prod[e]}) == [x for x in range(8) if ev[2] >> x & 1]
+            assert all(int(tasks[t][1]) == (2 if ev[1] == 1 else 1) for t in prod[e])
     # every task is reachable from exactly one queue position (chiplet / XCD groups) or from
     # the same position of every queue (device-wide groups)
     seen = np.zeros(len(tasks), int)

@@ -39,6 +39,26 @@ def test_two_layers_ragged_positions_with_lm_head(batch):
     check_new_kv(m, got[2], got[3], k, v)
 
 
+@pytest.mark.parametrize("batch,fma_max", [(5, 8), (8, 8), (3, 1), (4, 0)])
+def test_fma_mfma_switch_moved_by_environment(monkeypatch, batch, fma_max):
+    """FLEET_FMA_MAX_BATCH moves the batch at which the GEMMs switch from the FMA GEMV kernels
+    to the MFMA kernels: batch 5 and 8 on the FMA kernels, batch 3 and 4 on the MFMA ones."""
+    monkeypatch.setenv("FLEET_FMA_MAX_BATCH", str(fma_max))
+    print(f"decode 2 layers batch={batch} FLEET_FMA_MAX_BATCH={fma_max}", flush=True)
+    sh = si.reduced_shape(max_batch=batch, max_seq=160, n_layers=2, vocab=1024)
+    pos = np.random.default_rng(batch).integers(0, 160, batch).astype(np.int32)
+    m = Model(sh, seed=20 + batch, batch=batch, positions=pos)
+    (ho, lg), k, v = m.run_oracle()
+    f = F.fleet_create(sh.asdict(), m.w, 0, 0, 0)
+    g = F.parse_graph(F.fleet_graph_dump(f, batch))
+    assert g["header"]["path"] == (0 if batch <= fma_max else 1)
+    got = m.run_gpu(fleet=f)
+    F.fleet_destroy(f)
+    assert_close(got[0], ho, "hidden_out")
+    assert_close(got[1], lg, "logits")
+    check_new_kv(m, got[2], got[3], k, v)
+
+
 @pytest.mark.parametrize("sched,tile_m,flags", [(1, 0, 0), (0, 16, 0), (1, 16, 0),
                                                  (0, 0, F.FLAG_SINGLE_LEVEL), (0, 0, F.FLAG_SEPARATE_NORM),
                                                  (1, 0, F.FLAG_SEPARATE_NORM)])
