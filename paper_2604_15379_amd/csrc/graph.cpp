@@ -88,7 +88,9 @@ struct Builder {
   // One GEMM device-task.  Cooperative: one chiplet-task per XCD over a contiguous
   // slice of the output units (section 3.2, N-split).  Unaware: 2-D tiles
   // (unit group x m-tile) in N-major order, dealt to any worker.
-  int gemm_stage(int op, int wait_ev) {
+  // skip[x] (cooperative schedule only): the first skip[x] workers of XCD x take no units
+  // of this chiplet-task (they are still busy with the stage before it).
+  int gemm_stage(int op, int wait_ev, const std::vector<int>* skip = nullptr) {
     const int32_t* o = &g.ops[(size_t)op * OP_WORDS];
     const int U = o[O_N_UNITS], mt = o[O_M_TILES];
     int ev;
@@ -118,7 +120,7 @@ struct Builder {
       for (int x = 0; x < n_xcd; ++x) {
         int u0 = (int)((int64_t)U * x / n_xcd), u1 = (int)((int64_t)U * (x + 1) / n_xcd);
         if (u1 <= u0) continue;
-        int t = add_task(op, S_CHIPLET, x, u0, u1 - u0, 0, 0, wait_ev, ev);
+        int t = add_task(op, S_CHIPLET, x, u0, u1 - u0, skip ? (*skip)[x] : 0, 0, wait_ev, ev);
         push_q(x, t, 1, D_CHIPLET);
       }
     }
@@ -263,6 +265,19 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   // sooner) is slower than requesting the full depth everywhere.
   const int PRE2 = 3 << 10;
 
+  // FMA path: the workers that run an XCD's attention tasks (its first ranks: the tasks are
+  // dealt by rank) take no units of the O projection when they are at most half of the XCD's
+  // workers.  The others hold their O weights before attention ends, so the O stage does not
+  // wait for the attention workers to fetch theirs.
+  std::vector<int> o_skip(n_xcd, 0);
+  if (s.sched_mode == FLEET_SCHED_COOPERATIVE)
+    for (int x = 0; x < n_xcd; ++x) {
+      int n_att = 0;
+      for (int p = 0; p < batch * nkv; ++p) n_att += (p % n_xcd == x) ? S : 0;
+      const int wpx = n_workers / std::max(1, n_xcd);
+      o_skip[x] = 2 * n_att <= wpx ? n_att : 0;
+    }
+
   for (int l = 0; l < s.n_layers; ++l) {
     b.mark_all();
     int op_qkv;
@@ -288,7 +303,7 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
 
     int op_o = b.add_op(B_GEMM, l, E_RESID_F32, path, QD, H, ur, H / ur, mt, tm, BUF_ATT, BUF_X, 0, W_O,
                       (xmode(QD) << 8) | PRE2 | plan_bits(H / ur, QD, 1));
-    ev = b.gemm_stage(op_o, ev);
+    ev = b.gemm_stage(op_o, ev, path == P_FMA ? &o_skip : nullptr);
 
     // gate | up rows of one concatenated matrix; a unit is ur gate rows plus the
     // matching ur up rows (aux = row offset of the up half), SwiGLU in the epilogue

@@ -71,7 +71,8 @@ enum {
 enum XMode { X_GLOBAL = 0, X_LDS_COPY = 1, X_LDS_NORM = 2 };
 constexpr int GEMV_LDS_X_BYTES = 96 * 1024;   // LDS the FMA path may fill with activations
 // task word indices.  A0..A3 by body:
-//   GEMM chiplet-task : A0 first unit, A1 unit count            (tiles = units x m_tiles)
+//   GEMM chiplet-task : A0 first unit, A1 unit count, A2 workers (lowest ranks) that take
+//                       no units (FMA path)                    (tiles = units x m_tiles)
 //   GEMM CU-task      : A0 first unit, A1 unit count, A2 m-tile, A3 k-slice
 //   ATTN              : A0 batch row, A1 kv head, A2 split, A3 n_splits
 //   INGEST/RMSNORM/FINAL : A0 batch row

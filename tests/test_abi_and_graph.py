@@ -149,7 +149,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
                     best = ((cost, -G, KS), G, KS)
         return best[1] << 12 | best[2] << 16
 
-    def gemm_stage(o, wait):
+    def gemm_stage(o, wait, skip=None):
         U, m_tiles = ops[o][7], ops[o][8]
         ev = len(events)
         if sched == 1:
@@ -169,7 +169,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
             owners = [x for x in range(n_xcd) if bounds[x + 1] > bounds[x]]
             events.append([len(owners), 1, sum(1 << x for x in owners), len(owners)])
             for x in owners:
-                t = task(o, 2, x, [bounds[x], bounds[x + 1] - bounds[x], 0, 0], wait, ev)
+                t = task(o, 2, x, [bounds[x], bounds[x + 1] - bounds[x], skip[x] if skip else 0, 0], wait, ev)
                 queues[x].append([t, 1, 0, stage[0]])
         stage[0] += 1
         return ev
@@ -192,6 +192,14 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
     def xm(K):
         return ((1 if fma and batch * K * 2 <= LDS_X_BYTES else 0) << 8) | PRE
 
+    # FMA path, cooperative: the ranks that run an XCD's attention tasks take no O-projection
+    # units when they are at most half of the XCD's workers
+    o_skip = [0] * n_xcd
+    if sched == 0:
+        for x in range(n_xcd):
+            n_att = S * sum(1 for p in range(batch * nkv) if p % n_xcd == x)
+            o_skip[x] = n_att if 2 * n_att <= n_workers // n_xcd else 0
+
     for l in range(sh.n_layers):
         mark()
         if fuse:
@@ -205,7 +213,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
         att_items = [(p, [p // nkv, p % nkv, s, S]) for p in range(batch * nkv) for s in range(S)]
         ev = cu_stage(op(ATTN, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["QKV"], BUF["ATT"], S, WK["NONE"]), att_items, ev, 8)
         ev = gemm_stage(op(GEMM, l, 1, path, QD, H, ur, H // ur, mt, tm, BUF["ATT"], BUF["X"], 0, WK["O"],
-                           xm(QD) | plan(H // ur, QD, 1)), ev)
+                           xm(QD) | plan(H // ur, QD, 1)), ev, o_skip if fma else None)
         if fuse:
             o_gu = op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["X"], BUF["H"], Fd, WK["GU"],
                       WK["LN2"] | 2 << 8 | PRE)
