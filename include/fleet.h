@@ -45,7 +45,11 @@ enum fleet_err {
 /* Task scheduling (paper section 3.2 and Figure "tiling"). */
 enum fleet_sched {
   FLEET_SCHED_COOPERATIVE = 0, /* N-split per XCD, M-major tile order inside (M-tile) */
-  FLEET_SCHED_UNAWARE = 1      /* 2-D tiles dealt to any worker, N-major               */
+  FLEET_SCHED_UNAWARE = 1,     /* 2-D tiles dealt to any worker, N-major               */
+  FLEET_SCHED_MSPLIT = 2       /* the batch's m-tiles are split over the XCDs (section 3.2,
+                                  "M-split"): with T m-tiles, n_xcd / T XCDs share one
+                                  m-tile and split N among them; falls back to
+                                  COOPERATIVE where T < 2 or T does not divide n_xcd   */
 };
 
 enum fleet_flags {
@@ -55,7 +59,10 @@ enum fleet_flags {
                                   fused into the consuming GEMV); fleet_gemm: activations
                                   read from global memory instead of an LDS copy        */
   FLEET_FLAG_CHAINED = 8,      /* fleet_gemm: rep i+1 waits for rep i's event          */
-  FLEET_FLAG_TIMING = 16       /* record per-task timestamps only (no tickets: cheaper) */
+  FLEET_FLAG_TIMING = 16,      /* record per-task timestamps only (no tickets: cheaper) */
+  FLEET_FLAG_NO_SPLITK = 32,   /* MFMA GEMMs: never split K over workers (one k-slice)  */
+  FLEET_FLAG_NO_STREAM = 64    /* weight loads without the non-temporal (streaming)
+                                  cache hint (section 3.2, cache-modifier flavours)     */
 };
 
 typedef struct {

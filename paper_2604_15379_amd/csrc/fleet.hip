@@ -547,7 +547,7 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const
                int32_t sched_mode, int32_t tile_m, int32_t flags, int32_t reps, void* stream, float* elapsed_ms) {
   if (B < 1 || B > 64 || K < 32 || K % 32 || N < 16 || N % 16 || !x || !w_copies || n_copies < 1 || !y || reps < 1 || reps > 4096)
     return FLEET_EINVAL;
-  if (sched_mode != FLEET_SCHED_COOPERATIVE && sched_mode != FLEET_SCHED_UNAWARE) return FLEET_EINVAL;
+  if (sched_mode < FLEET_SCHED_COOPERATIVE || sched_mode > FLEET_SCHED_MSPLIT) return FLEET_EINVAL;
   if (tile_m != 0 && tile_m != 16 && tile_m != 32 && tile_m != 64) return FLEET_EINVAL;
   for (int i = 0; i < n_copies; ++i) if (!w_copies[i]) return FLEET_EINVAL;
   DevInfo info;

@@ -7,6 +7,11 @@
 
 namespace fleetg {
 
+// M-split applies to an operator with T >= 2 m-tiles where T divides the XCD count
+static bool msplit_applies(int sched, int path, int m_tiles, int n_xcd) {
+  return sched == FLEET_SCHED_MSPLIT && path == P_MFMA && m_tiles >= 2 && n_xcd % m_tiles == 0;
+}
+
 namespace {
 
 struct Builder {
@@ -110,6 +115,22 @@ struct Builder {
             add_task(op, S_CU, -1, u0, cnt, m, ks, wait_ev, ev);
           }
       for (int x = 0; x < n_xcd; ++x) push_q(x, first, ng * mt * ksn, D_DEV_RR);
+    } else if (msplit_applies(sched, o[O_PATH], mt, n_xcd)) {
+      // M-split: XCD x works on m-tile x / xpm only (A3 = m-tile + 1) and on the
+      // (x % xpm)-th of xpm slices of the units
+      const int xpm = n_xcd / mt;
+      int mask = 0, nx = 0;
+      for (int x = 0; x < n_xcd; ++x) {
+        int part = x % xpm, u0 = (int)((int64_t)U * part / xpm), u1 = (int)((int64_t)U * (part + 1) / xpm);
+        if (u1 > u0) { mask |= 1 << x; ++nx; }
+      }
+      ev = add_event(nx, EV_TWO_LEVEL, mask, nx);
+      for (int x = 0; x < n_xcd; ++x) {
+        int part = x % xpm, u0 = (int)((int64_t)U * part / xpm), u1 = (int)((int64_t)U * (part + 1) / xpm);
+        if (u1 <= u0) continue;
+        int t = add_task(op, S_CHIPLET, x, u0, u1 - u0, 0, x / xpm + 1, wait_ev, ev);
+        push_q(x, t, 1, D_CHIPLET);
+      }
     } else {
       int mask = 0, nx = 0;
       for (int x = 0; x < n_xcd; ++x) {
@@ -167,19 +188,22 @@ std::vector<int32_t> Graph::serialize() const {
   return out;
 }
 
+int mfma_blocks(int tile_m) { return tile_m <= 16 ? 1 : tile_m <= 32 ? 2 : 4; }
+
 // Tile plan of an MFMA GEMM operator: G units per tile and KS k-slices, chosen so that the
-// tiles of one XCD's unit slice keep its workers equally busy and the tiles are tall:
-// minimise ceil(tiles / workers) * (G + 2) / KS -- a tile of G units costs about G + 2,
-// because the weight bytes a worker keeps in flight grow with G and the activations are
-// read once per tile -- then prefer more units per tile, then fewer slices.
-MfmaPlan plan_mfma(int n_units, int K, int nb, int mt_blocks, int m_tiles, int n_xcd, int n_workers) {
+// tiles of one XCD's unit slice (ux units, m_tiles m-tiles each) keep its wpx workers equally
+// busy and the tiles are tall: minimise ceil(tiles / workers) * (G + 2) / KS -- a tile of G
+// units costs about G + 2, because the weight bytes a worker keeps in flight grow with G and
+// the activations are read once per tile -- then prefer more units per tile, then fewer
+// slices.  allow_split = false: one k-slice only.
+MfmaPlan plan_mfma(int ux, int wpx, int K, int nb, int mt_blocks, int m_tiles, bool allow_split) {
   const int gmax = std::max(1, ((mt_blocks >= 4 || nb == 2) ? 6 : 8) / nb);
-  const int ux = (n_units + n_xcd - 1) / std::max(1, n_xcd), wpx = std::max(1, n_workers / std::max(1, n_xcd));
+  ux = std::max(1, ux); wpx = std::max(1, wpx);
   MfmaPlan best{1, 1};
   long best_cost = -1;
-  for (int G = 1; G <= std::min(gmax, std::max(1, ux)); ++G)
+  for (int G = 1; G <= std::min(gmax, ux); ++G)
     for (int KS = 1; KS <= 8; KS *= 2) {
-      if (KS > 1 && (K % (KS * 256) != 0 || (long)n_units * m_tiles > GEMM_TILE_COUNTERS)) continue;
+      if (KS > 1 && (!allow_split || K % (KS * 256) != 0)) continue;
       const long tiles = (long)((ux + G - 1) / G) * KS * m_tiles;
       const long cost = ((tiles + wpx - 1) / wpx) * (G + 2) * (8 / KS);
       if (best_cost < 0 || cost < best_cost || (cost == best_cost && (G > best.G || (G == best.G && KS < best.KS)))) {
@@ -187,6 +211,17 @@ MfmaPlan plan_mfma(int n_units, int K, int nb, int mt_blocks, int m_tiles, int n
       }
     }
   return best;
+}
+
+// the plan of an operator with n_units units under the given schedule
+static MfmaPlan plan_for(int sched, int flags, int n_units, int K, int nb, int tile_m, int m_tiles, int n_xcd, int n_workers) {
+  const bool split_ok = !(flags & FLEET_FLAG_NO_SPLITK) && (long)n_units * m_tiles <= GEMM_TILE_COUNTERS;
+  const int wpx = n_workers / std::max(1, n_xcd);
+  if (msplit_applies(sched, P_MFMA, m_tiles, n_xcd)) {   // n_xcd / m_tiles XCDs share one m-tile and split N
+    const int xpm = n_xcd / m_tiles;
+    return plan_mfma((n_units + xpm - 1) / xpm, wpx, K, nb, mfma_blocks(tile_m), 1, split_ok);
+  }
+  return plan_mfma((n_units + n_xcd - 1) / std::max(1, n_xcd), wpx, K, nb, mfma_blocks(tile_m), m_tiles, split_ok);
 }
 
 // Largest batch that runs the FMA GEMV kernels.  Measured on MI355X the MFMA kernels win from
@@ -198,8 +233,6 @@ static int fma_max() {
   return std::min(8, std::max(0, atoi(e)));
 }
 int fma_max_batch() { return fma_max(); }
-
-int mfma_blocks(int tile_m) { return tile_m <= 16 ? 1 : tile_m <= 32 ? 2 : 4; }
 
 int resolve_tile_m(int batch, int tile_m) {
   if (batch <= fma_max()) return batch;  // FMA GEMV path: one tile holds the whole batch
@@ -223,7 +256,7 @@ int check_shape(const fleet_shape_t& s) {
   if (s.hidden % 32 || s.ffn % 32) return FLEET_EINVAL;
   if (s.vocab < 0 || s.vocab % 16) return FLEET_EINVAL;
   if (s.max_batch < 1 || s.max_batch > 64 || s.max_seq < 1) return FLEET_EINVAL;
-  if (s.sched_mode != FLEET_SCHED_COOPERATIVE && s.sched_mode != FLEET_SCHED_UNAWARE) return FLEET_EINVAL;
+  if (s.sched_mode < FLEET_SCHED_COOPERATIVE || s.sched_mode > FLEET_SCHED_MSPLIT) return FLEET_EINVAL;
   if (s.tile_m != 0 && s.tile_m != 16 && s.tile_m != 32 && s.tile_m != 64) return FLEET_EINVAL;
   if (!(s.rms_eps >= 0.f) || !(s.rope_theta > 0.f)) return FLEET_EINVAL;
   return FLEET_OK;
@@ -242,7 +275,7 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   // MFMA operators carry their tile plan in aux2: bits 12..15 units per tile, 16..19 k-slices
   auto plan_bits = [&](int n_units, int K, int nb) {
     if (path != P_MFMA) return 0;
-    const MfmaPlan pl = plan_mfma(n_units, K, nb, mfma_blocks(tm), mt, n_xcd, n_workers);
+    const MfmaPlan pl = plan_for(s.sched_mode, s.flags, n_units, K, nb, tm, mt, n_xcd, n_workers);
     return (pl.G << 12) | (pl.KS << 16);
   };
 
@@ -270,7 +303,7 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   // workers.  The others hold their O weights before attention ends, so the O stage does not
   // wait for the attention workers to fetch theirs.
   std::vector<int> o_skip(n_xcd, 0);
-  if (s.sched_mode == FLEET_SCHED_COOPERATIVE)
+  if (s.sched_mode != FLEET_SCHED_UNAWARE)
     for (int x = 0; x < n_xcd; ++x) {
       int n_att = 0;
       for (int p = 0; p < batch * nkv; ++p) n_att += (p % n_xcd == x) ? S : 0;
@@ -353,7 +386,7 @@ Graph build_gemm_graph(int B, int K, int N, int sched_mode, int tile_m, int flag
   // their arrivals in one of two counter sets (bit 20 of aux2), so a repetition of such a
   // plan waits for the one before the previous: at most two are in flight.
   MfmaPlan pl{1, 1};
-  if (path == P_MFMA) pl = plan_mfma(N / ur, K, 1, mfma_blocks(tm), mt, n_xcd, n_workers);
+  if (path == P_MFMA) pl = plan_for(sched_mode, flags, N / ur, K, 1, tm, mt, n_xcd, n_workers);
   std::vector<int> evs;
   for (int r = 0; r < reps; ++r) {
     const int xm = path == P_FMA && (int64_t)B * K * 2 <= GEMV_LDS_X_BYTES && !(flags & FLEET_FLAG_SEPARATE_NORM)

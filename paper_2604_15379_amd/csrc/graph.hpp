@@ -72,7 +72,8 @@ enum XMode { X_GLOBAL = 0, X_LDS_COPY = 1, X_LDS_NORM = 2 };
 constexpr int GEMV_LDS_X_BYTES = 96 * 1024;   // LDS the FMA path may fill with activations
 // task word indices.  A0..A3 by body:
 //   GEMM chiplet-task : A0 first unit, A1 unit count, A2 workers (lowest ranks) that take
-//                       no units (FMA path)                    (tiles = units x m_tiles)
+//                       no units (FMA path), A3 = m-tile + 1 if the task covers one m-tile
+//                       only (M-split), else 0                 (tiles = units x m_tiles)
 //   GEMM CU-task      : A0 first unit, A1 unit count, A2 m-tile, A3 k-slice
 //   ATTN              : A0 batch row, A1 kv head, A2 split, A3 n_splits
 //   INGEST/RMSNORM/FINAL : A0 batch row
@@ -96,7 +97,7 @@ struct Graph {
 // arrival counter per (first unit of a tile, m-tile), GEMM_TILE_COUNTERS at most
 constexpr int GEMM_TILE_COUNTERS = 4096;
 struct MfmaPlan { int G, KS; };
-MfmaPlan plan_mfma(int n_units, int K, int nb, int mt_blocks, int m_tiles, int n_xcd, int n_workers);
+MfmaPlan plan_mfma(int units_per_xcd, int workers_per_xcd, int K, int nb, int mt_blocks, int m_tiles, bool allow_split);
 // 16-row blocks of batch rows the MFMA kernel for tile height tile_m accumulates (1, 2 or 4)
 int mfma_blocks(int tile_m);
 // largest batch that runs the FMA GEMV kernels (larger batches run the MFMA kernels)

@@ -129,6 +129,10 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
         stage[0] += 1
         return ev
 
+    def msplit(m_tiles):
+        """M-split applies on the MFMA path when the m-tiles (>= 2) divide the XCD count."""
+        return sched == 2 and not fma and m_tiles >= 2 and n_xcd % m_tiles == 0
+
     def plan(U, K, nb):
         """MFMA tile plan: units per tile G and k-slices KS keeping one XCD's workers equally
         busy with tall tiles (a tile of G units is charged G + 2); ties go to more units per
@@ -137,13 +141,19 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
             return 0
         blocks = 1 if tm <= 16 else 2 if tm <= 32 else 4
         gmax = max(1, (6 if blocks >= 4 or nb == 2 else 8) // nb)
-        ux, wpx = -(-U // n_xcd), max(1, n_workers // n_xcd)
+        split_ok = not (flags & 32) and U * mt <= 4096
+        wpx = max(1, n_workers // n_xcd)
+        if msplit(mt):      # n_xcd / mt XCDs share one m-tile and split the units
+            xpm = n_xcd // mt
+            ux, tiles_m = -(-U // xpm), 1
+        else:
+            ux, tiles_m = -(-U // n_xcd), mt
         best = None
         for G in range(1, min(gmax, max(1, ux)) + 1):
             for KS in (1, 2, 4, 8):
-                if KS > 1 and (K % (KS * 256) or U * mt > 4096):
+                if KS > 1 and (not split_ok or K % (KS * 256)):
                     continue
-                tiles = -(-ux // G) * KS * mt
+                tiles = -(-ux // G) * KS * tiles_m
                 cost = -(-tiles // wpx) * (G + 2) * (8 // KS)
                 if best is None or (cost, -G, KS) < best[0]:
                     best = ((cost, -G, KS), G, KS)
@@ -164,6 +174,15 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
                         task(o, 1, -1, [g * cu, min(cu, U - g * cu), m, ks], wait, ev)
             for x in range(n_xcd):
                 queues[x].append([first, ng * m_tiles * ksn, 2, stage[0]])
+        elif msplit(m_tiles):
+            xpm = n_xcd // m_tiles
+            bounds = [U * part // xpm for part in range(xpm + 1)]
+            owners = [x for x in range(n_xcd) if bounds[x % xpm + 1] > bounds[x % xpm]]
+            events.append([len(owners), 1, sum(1 << x for x in owners), len(owners)])
+            for x in owners:
+                part = x % xpm
+                t = task(o, 2, x, [bounds[part], bounds[part + 1] - bounds[part], 0, x // xpm + 1], wait, ev)
+                queues[x].append([t, 1, 0, stage[0]])
         else:
             bounds = [U * x // n_xcd for x in range(n_xcd + 1)]
             owners = [x for x in range(n_xcd) if bounds[x + 1] > bounds[x]]
@@ -195,7 +214,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
     # FMA path, cooperative: the ranks that run an XCD's attention tasks take no O-projection
     # units when they are at most half of the XCD's workers
     o_skip = [0] * n_xcd
-    if sched == 0:
+    if sched != 1:
         for x in range(n_xcd):
             n_att = S * sum(1 for p in range(batch * nkv) if p % n_xcd == x)
             o_skip[x] = n_att if 2 * n_att <= n_workers // n_xcd else 0
@@ -247,7 +266,8 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("sched,tile_m,flags", [(0, 0, 0), (0, 16, 0), (1, 0, 0), (1, 16, 0), (0, 0, 4), (1, 0, 4)])
+@pytest.mark.parametrize("sched,tile_m,flags", [(0, 0, 0), (0, 16, 0), (1, 0, 0), (1, 16, 0), (0, 0, 4), (1, 0, 4),
+                                                 (2, 16, 0), (2, 32, 0), (0, 16, 32), (1, 0, 32)])
 def test_builder_equals_independent_derivation(sched, tile_m, flags):
     for sh, batches, n_xcd, n_workers in CASES:
         for b in batches:
@@ -268,7 +288,7 @@ def _producers(g):
     return prod
 
 
-@pytest.mark.parametrize("sched", [0, 1])
+@pytest.mark.parametrize("sched", [0, 1, 2])
 @pytest.mark.parametrize("batch", [1, 8, 32, 64])
 def test_graph_invariants(batch, sched):
     sh = si.qwen3_8b_shape(64, 4097, n_layers=2)
@@ -311,7 +331,9 @@ def test_graph_invariants(batch, sched):
         ksn = max(1, op[15] >> 16 & 15) if op[3] == 1 else 1
         cover = np.zeros((op[7], op[8], ksn), int)
         for t in tasks[tasks[:, 0] == o]:
-            if t[1] == 2:
+            if t[1] == 2 and t[6] > 0:
+                cover[t[3]:t[3] + t[4], t[6] - 1, :] += 1   # M-split: one m-tile of the task's units
+            elif t[1] == 2:
                 cover[t[3]:t[3] + t[4], :, :] += 1      # a chiplet-task walks all its tiles
             else:
                 cover[t[3]:t[3] + t[4], t[5], t[6]] += 1

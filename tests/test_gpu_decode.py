@@ -61,7 +61,10 @@ def test_fma_mfma_switch_moved_by_environment(monkeypatch, batch, fma_max):
 
 @pytest.mark.parametrize("sched,tile_m,flags", [(1, 0, 0), (0, 16, 0), (1, 16, 0),
                                                  (0, 0, F.FLAG_SINGLE_LEVEL), (0, 0, F.FLAG_SEPARATE_NORM),
-                                                 (1, 0, F.FLAG_SEPARATE_NORM)])
+                                                 (1, 0, F.FLAG_SEPARATE_NORM),
+                                                 (F.SCHED_MSPLIT, 16, 0), (F.SCHED_MSPLIT, 0, 0),
+                                                 (0, 0, F.FLAG_NO_SPLITK), (1, 16, F.FLAG_NO_SPLITK),
+                                                 (0, 0, F.FLAG_NO_STREAM)])
 @pytest.mark.parametrize("batch", [3, 40])
 def test_schedules_agree_with_oracle(batch, sched, tile_m, flags):
     print(f"decode modes batch={batch} sched={sched} tile_m={tile_m} flags={flags}", flush=True)

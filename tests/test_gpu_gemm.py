@@ -42,7 +42,8 @@ def test_gemm_small_shapes(B, K, N):
 
 @pytest.mark.parametrize("sched,tile_m,flags", [(0, 16, 0), (1, 16, 0), (1, 0, 0), (0, 32, 0),
                                                  (0, 16, F.FLAG_SINGLE_LEVEL), (0, 0, F.FLAG_CHAINED),
-                                                 (0, 0, F.FLAG_SEPARATE_NORM)])
+                                                 (0, 0, F.FLAG_SEPARATE_NORM), (F.SCHED_MSPLIT, 16, 0),
+                                                 (0, 0, F.FLAG_NO_SPLITK), (0, 0, F.FLAG_NO_STREAM)])
 @pytest.mark.parametrize("B", [4, 48])
 def test_gemm_schedules_and_tiles(B, sched, tile_m, flags):
     print(f"gemm modes B={B} sched={sched} tile_m={tile_m} flags={flags}", flush=True)
@@ -63,6 +64,12 @@ def test_cooperative_and_unaware_give_identical_bits():
         a, _, _ = _run(B, 1024, N, 0, tile_m)
         b, _, _ = _run(B, 1024, N, 1, tile_m)
         assert np.array_equal(a, b), f"B={B} tile_m={tile_m} N={N}"
+    # the M-split schedule uses the same k-slices only if its plan agrees; with split-K off
+    # every schedule sums a tile's K range in one piece
+    for B, tile_m in ((64, 16), (48, 16)):
+        a, _, _ = _run(B, 1024, 6144, 0, tile_m, F.FLAG_NO_SPLITK)
+        c, _, _ = _run(B, 1024, 6144, F.SCHED_MSPLIT, tile_m, F.FLAG_NO_SPLITK)
+        assert np.array_equal(a, c), f"M-split B={B}"
 
 
 # the Qwen3-8B GEMM shapes of the sweep
