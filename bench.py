@@ -45,7 +45,7 @@ def parse():
     ap.add_argument("--kv", type=int, default=1024, help="valid KV slots per sequence before the step")
     ap.add_argument("--kv-min", type=int, default=0, help="if > 0, per-sequence lengths uniform in [kv-min, kv]")
     ap.add_argument("--layers", type=int, default=36)
-    ap.add_argument("--sched", type=int, default=0, help="0 cooperative (XCD), 1 chiplet-unaware")
+    ap.add_argument("--sched", type=int, default=0, help="0 cooperative (XCD), 1 chiplet-unaware, 2 M-split")
     ap.add_argument("--tile-m", type=int, default=0)
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--seed", type=int, default=2)
@@ -188,7 +188,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"Qwen3-8B-shaped decode step, {a.layers} layers + LM head, batch {B}, "
                                f"KV {a.kv_min or a.kv}..{a.kv} per sequence, random bf16 weights (seed {a.seed})",
-                   "batch": B, "kv_len": a.kv, "sched_mode": ["cooperative", "unaware"][a.sched],
+                   "batch": B, "kv_len": a.kv, "sched_mode": ["cooperative", "unaware", "m-split"][a.sched],
                    "tile_m": a.tile_m, "flags": a.flags, "tokens_per_s": B / (ms * 1e-3)},
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gbps / HBM_PEAK_GBPS, "traffic": traffic,

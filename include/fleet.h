@@ -55,7 +55,7 @@ enum fleet_sched {
 enum fleet_flags {
   FLEET_FLAG_TRACE = 1,        /* record per-task tickets and timestamps               */
   FLEET_FLAG_SINGLE_LEVEL = 2, /* every worker signals the device counter itself       */
-  FLEET_FLAG_SEPARATE_NORM = 4,/* RMSNorm as CU-tasks also at batch <= 8 (default there:
+  FLEET_FLAG_SEPARATE_NORM = 4,/* RMSNorm as CU-tasks also on the FMA path (default there:
                                   fused into the consuming GEMV); fleet_gemm: activations
                                   read from global memory instead of an LDS copy        */
   FLEET_FLAG_CHAINED = 8,      /* fleet_gemm: rep i+1 waits for rep i's event          */
@@ -73,13 +73,21 @@ typedef struct {
   float rms_eps;      /* 1e-6                                                            */
   float rope_theta;   /* 1e6                                                             */
   int32_t sched_mode; /* enum fleet_sched                                                */
-  int32_t tile_m;     /* GEMM tile height along the batch for batch > 8: 16, 32, 64, or
-                         0 = whole batch rounded up to 16 (reads each weight once)       */
+  int32_t tile_m;     /* GEMM tile height along the batch on the MFMA path: 16, 32, 64, or
+                         0 = whole batch rounded up to 16 (reads each weight once).
+                         Batches up to 4 run FMA GEMV kernels, larger ones bf16 MFMA
+                         kernels; the environment variable FLEET_FMA_MAX_BATCH (0..8),
+                         read when a graph is built, moves that switch                  */
   int32_t flags;      /* enum fleet_flags                                                */
 } fleet_shape_t;
 
 /* All device pointers, bf16, caller-owned, read-only, alive until fleet_destroy.
- * The per-layer members are HOST arrays of n_layers device pointers. */
+ * The per-layer members are HOST arrays of n_layers device pointers.
+ * The FMA GEMV kernels (small batches) read these matrices in place.  When max_batch
+ * reaches the MFMA kernels (see tile_m), fleet_create also makes a private repacked copy
+ * of wqkv, wo, wgu, wdown and lm_head (same size again in device memory), which those
+ * kernels read: a change the caller makes to these matrices after fleet_create is then
+ * seen by small batches only. */
 typedef struct {
   const void *embed;          /* [vocab, hidden] or NULL                                 */
   const void *const *ln1;     /* [hidden]                                                */
@@ -107,7 +115,8 @@ typedef struct {
 
 /*
  * fleet_create: validate the shape, probe the device (CU count, XCD count),
- * allocate descriptors, counters and scratch activations, build the RoPE table.
+ * allocate descriptors, counters and scratch activations, build the RoPE table, and
+ * (max_batch on the MFMA path) repack the GEMM weights into a private copy.
  * Paper section 4.3 (task registration at model load).  *out is set on success.
  * Requirements: head_dim == 128, hidden/ffn/(nq*head_dim) multiples of 16,
  * n_q_heads a multiple of n_kv_heads with ratio <= 4, vocab a multiple of 16,
@@ -163,7 +172,10 @@ int fleet_destroy(fleet_t *f);
  *   elapsed_ms  HOST float or NULL: time of the one kernel launch that runs all
  *             reps, measured with HIP events on `stream`
  * K a multiple of 32, N of 16, 1 <= B <= 64.  Synchronous: returns after the
- * kernel has finished (it allocates and frees its own descriptors).
+ * kernel has finished (it allocates and frees its own descriptors and, on the MFMA
+ * path, packed copies of x and of every weight copy).  Repetitions are independent
+ * of each other unless FLEET_FLAG_CHAINED is set; with a split-K plan a repetition
+ * waits for the one before the previous (two sets of arrival counters).
  */
 int fleet_gemm(int32_t B, int32_t K, int32_t N, const void *x, const void *const *w_copies,
                int32_t n_copies, float *y, int32_t sched_mode, int32_t tile_m, int32_t flags,

@@ -334,8 +334,15 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
                     // signal directly: two-level pays only with many tasks per XCD
                     ATTN_TWO_LEVEL_MIN_PER_XCD);
 
-    int op_o = b.add_op(B_GEMM, l, E_RESID_F32, path, QD, H, ur, H / ur, mt, tm, BUF_ATT, BUF_X, 0, W_O,
-                      (xmode(QD) << 8) | PRE2 | plan_bits(H / ur, QD, 1));
+    // FMA path, cooperative: the O projection's idle workers warm the L2 with the first weight
+    // block of their gate/up task while attention runs (aux = gate rows, low byte of aux2 =
+    // W_GU: the op's second pointer is that matrix)
+    // -- worth it only while most of the XCD idles through attention: attention workers at
+    // most a quarter of each XCD's workers (batch 1 of the 8-KV-head model)
+    bool warm_gu = path == P_FMA && s.sched_mode != FLEET_SCHED_UNAWARE;
+    for (int x = 0; x < n_xcd; ++x) warm_gu = warm_gu && o_skip[x] > 0 && 4 * o_skip[x] <= n_workers / std::max(1, n_xcd);
+    int op_o = b.add_op(B_GEMM, l, E_RESID_F32, path, QD, H, ur, H / ur, mt, tm, BUF_ATT, BUF_X, warm_gu ? F : 0, W_O,
+                      (warm_gu ? W_GU : 0) | (xmode(QD) << 8) | PRE2 | plan_bits(H / ur, QD, 1));
     ev = b.gemm_stage(op_o, ev, path == P_FMA ? &o_skip : nullptr);
 
     // gate | up rows of one concatenated matrix; a unit is ur gate rows plus the

@@ -63,7 +63,9 @@ enum {
   O_BODY = 0, O_LAYER, O_EPI, O_PATH, O_K, O_N, O_UNIT_ROWS, O_N_UNITS, O_M_TILES, O_TILE_M,
   O_IN_BUF, O_OUT_BUF, O_AUX, O_WKIND, O_BATCH, O_AUX2
 };
-// O_AUX2 of a GEMM op: low byte = WKind of the fused RMSNorm gain (W_NONE if none),
+// O_AUX2 of a GEMM op: low byte = WKind of the op's second pointer (W_NONE if none): the gain
+// of the fused RMSNorm (activation mode X_LDS_NORM), else the weights of the next GEMM, whose
+// first block the op's idle workers pull into the L2 (O_AUX then holds that matrix's gate rows),
 // bits 8..9 = activation mode of the FMA path (XMode), bits 10..11 = weight blocks the FMA
 // path requests before its dependency wait (0..3); MFMA path: bits 12..15 = units per tile,
 // bits 16..19 = k-slices of the split-K plan (1 = no split), bit 20 = counter set of the

@@ -231,8 +231,13 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
         ev = gemm_stage(o_qkv, ev)
         att_items = [(p, [p // nkv, p % nkv, s, S]) for p in range(batch * nkv) for s in range(S)]
         ev = cu_stage(op(ATTN, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["QKV"], BUF["ATT"], S, WK["NONE"]), att_items, ev, 8)
-        ev = gemm_stage(op(GEMM, l, 1, path, QD, H, ur, H // ur, mt, tm, BUF["ATT"], BUF["X"], 0, WK["O"],
-                           xm(QD) | plan(H // ur, QD, 1)), ev, o_skip if fma else None)
+        # FMA path, cooperative: the O projection carries the gate/up matrix as second pointer
+        # (low byte of aux2) and its gate rows (aux): idle workers warm the L2 with it
+        # -- only where attention keeps at most a quarter of every XCD's workers busy
+        warm = fma and sched != 1 and all(0 < k and 4 * k <= n_workers // n_xcd for k in o_skip)
+        ev = gemm_stage(op(GEMM, l, 1, path, QD, H, ur, H // ur, mt, tm, BUF["ATT"], BUF["X"], Fd if warm else 0,
+                           WK["O"], (WK["GU"] if warm else 0) | xm(QD) | plan(H // ur, QD, 1)), ev,
+                        o_skip if fma else None)
         if fuse:
             o_gu = op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["X"], BUF["H"], Fd, WK["GU"],
                       WK["LN2"] | 2 << 8 | PRE)
