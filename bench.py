@@ -24,15 +24,24 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the persistent kernel (reads + writes) from the rocprofv3
 # FETCH_SIZE and WRITE_SIZE passes summarised in
 # profiles/fleet_persistent_kernel_counters_qwen3_8b_b1_to_b64.md, after scaling by what the
-# same counters read for a plain copy of known size.  Key: (batch, kv, kv_min, sched, tile_m)
+# same counters read for a plain copy of known size.  Key: (batch, kv, kv_min, sched, tile_m, flags)
 # at 36 layers and seed 2; any other workload reports null unless --traffic-bytes is given.
 MEASURED_TRAFFIC = {
-    (1, 1024, 0, 0, 0): 15399382016, (1, 1024, 0, 1, 0): 15362461565,
-    (8, 2048, 1024, 0, 0): 16999640710, (8, 2048, 1024, 1, 0): 17051909693,
-    (32, 2048, 1024, 0, 16): 26394901367, (32, 2048, 1024, 1, 16): 39628918412,
-    (32, 2048, 1024, 0, 0): 24798197758,
-    (64, 4096, 0, 0, 16): 59197543900, (64, 4096, 0, 1, 16): 104306692029,
-    (64, 4096, 0, 0, 0): 62541383476,
+    (1, 1024, 0, 0, 0, 0): 15440332825,
+    (1, 1024, 0, 1, 0, 0): 15461265491,
+    (1, 1024, 0, 0, 0, 64): 16254256402,
+    (8, 2048, 1024, 0, 0, 0): 17313596060,
+    (8, 2048, 1024, 1, 0, 0): 17375794911,
+    (32, 2048, 1024, 0, 0, 0): 23402983460,
+    (32, 2048, 1024, 0, 16, 0): 26000035665,
+    (32, 2048, 1024, 1, 16, 0): 34632305872,
+    (32, 2048, 1024, 2, 16, 0): 38188532918,
+    (64, 4096, 0, 0, 0, 0): 56764363720,
+    (64, 4096, 0, 0, 16, 0): 60882509420,
+    (64, 4096, 0, 1, 16, 0): 86866980401,
+    (64, 4096, 0, 2, 16, 0): 100676571220,
+    (64, 4096, 0, 0, 16, 32): 58229367874,
+    (64, 4096, 0, 0, 16, 64): 56639297422,
 }
 
 
@@ -179,8 +188,8 @@ def main():
 
     step_bytes = F.fleet_step_bytes(shape.asdict(), B, pos_host)
     traffic = a.traffic_bytes
-    if traffic is None and a.layers == 36 and a.seed == 2 and a.flags == 0:
-        traffic = MEASURED_TRAFFIC.get((B, a.kv, a.kv_min, a.sched, a.tile_m))
+    if traffic is None and a.layers == 36 and a.seed == 2:
+        traffic = MEASURED_TRAFFIC.get((B, a.kv, a.kv_min, a.sched, a.tile_m, a.flags))
     gbps = step_bytes / (ms * 1e-3) / 1e9
     out = {
         "metric": "decode_step_latency_us", "value": ms * 1e3, "unit": "us", "n_gpus": 1,
