@@ -91,10 +91,9 @@ def test_embedding_gather_input():
 def test_dependency_order_from_trace():
     """Every task ran exactly once (every tile of a chiplet-task once) and no task started
     before all tasks signalling its wait event had ended: tickets from one device counter."""
-    for sched in (0, 1):
-        batch = 6
+    for sched, batch in ((0, 6), (1, 6), (2, 6), (0, 3), (1, 3)):   # MFMA path (6) and FMA path (3)
         sh = si.reduced_shape(max_batch=batch, max_seq=100, n_layers=2, vocab=512)
-        m = Model(sh, seed=8, batch=batch, positions=[5, 99, 0, 50, 64, 63])
+        m = Model(sh, seed=8, batch=batch, positions=[5, 99, 0, 50, 64, 63][:batch])
         got = m.run_gpu(sched, 0, F.FLAG_TRACE)
         trace, g = got[5], got[6]
         tasks, events = g["tasks"], g["events"]
@@ -117,6 +116,31 @@ def test_dependency_order_from_trace():
             w = tasks[r[0], 7]
             if w >= 0:
                 assert end_of_event[w] < r[4], f"task {r[0]} started before event {w} completed"
+
+
+def test_dependency_order_from_timestamps():
+    """FLEET_FLAG_TIMING records wall-clock stamps instead of tickets (all workers read one
+    constant-rate counter): no task starts before the tasks signalling its wait event ended."""
+    batch = 9
+    sh = si.reduced_shape(max_batch=batch, max_seq=100, n_layers=2, vocab=512)
+    m = Model(sh, seed=9, batch=batch, positions=list(range(5, 5 + batch)))
+    f = F.fleet_create(sh.asdict(), m.w, 0, 0, F.FLAG_TIMING)
+    got = m.run_gpu(fleet=f)
+    trace, g = F.fleet_trace_read(f), F.parse_graph(F.fleet_graph_dump(f, batch))
+    F.fleet_destroy(f)
+    tasks, events = g["tasks"], g["events"]
+    assert len(trace) > 0 and (trace[:, 7] >= trace[:, 6]).all()
+    end_of_event = np.full(len(events), -1, np.int64)
+    for r in trace:
+        e = tasks[r[0], 8]
+        if e >= 0:
+            end_of_event[e] = max(end_of_event[e], r[7])
+    for r in trace:
+        w = tasks[r[0], 7]
+        if w >= 0:
+            assert end_of_event[w] <= r[6], f"task {r[0]} started before event {w} completed"
+    (ho, lg), _, _ = m.run_oracle()
+    assert_close(got[0], ho, "hidden_out")
 
 
 def test_timeout_is_reported_not_hung(monkeypatch):

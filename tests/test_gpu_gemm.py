@@ -80,3 +80,13 @@ def test_gemm_qwen3_shapes(B, K, N):
     y, ref, ms = _run(B, K, N)
     print(f"  {ms * 1e3:.1f} us", flush=True)
     assert_close(y, ref, f"gemm B={B} K={K} N={N}", tol=1e-3)
+
+
+def test_fleet_copy_moves_bytes():
+    """The calibration copy kernel copies exactly the bytes it is asked to."""
+    g = si.Gen(11, "cuda")
+    src = g.normal_bf16((1 << 20,), 1.0)
+    dst = torch.zeros_like(src)
+    F.fleet_copy(dst, src, src.numel() * 2, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(src.view(torch.int16), dst.view(torch.int16))
