@@ -61,8 +61,11 @@ enum fleet_flags {
   FLEET_FLAG_CHAINED = 8,      /* fleet_gemm: rep i+1 waits for rep i's event          */
   FLEET_FLAG_TIMING = 16,      /* record per-task timestamps only (no tickets: cheaper) */
   FLEET_FLAG_NO_SPLITK = 32,   /* MFMA GEMMs: never split K over workers (one k-slice)  */
-  FLEET_FLAG_NO_STREAM = 64    /* weight loads without the non-temporal (streaming)
+  FLEET_FLAG_NO_STREAM = 64,   /* weight loads without the non-temporal (streaming)
                                   cache hint (section 3.2, cache-modifier flavours)     */
+  FLEET_FLAG_NO_RESIDENT = 128 /* MFMA GEMMs: never hold a worker's whole weight share in
+                                  registers across the dependency wait (small GEMMs then
+                                  use split-K tiles)                                    */
 };
 
 typedef struct {

@@ -199,7 +199,7 @@ int mfma_blocks(int tile_m) { return tile_m <= 16 ? 1 : tile_m <= 32 ? 2 : 4; }
 MfmaPlan plan_mfma(int ux, int wpx, int K, int nb, int mt_blocks, int m_tiles, bool allow_split) {
   const int gmax = std::max(1, ((mt_blocks >= 4 || nb == 2) ? 6 : 8) / nb);
   ux = std::max(1, ux); wpx = std::max(1, wpx);
-  MfmaPlan best{1, 1};
+  MfmaPlan best{1, 1, 0};
   long best_cost = -1;
   for (int G = 1; G <= std::min(gmax, ux); ++G)
     for (int KS = 1; KS <= 8; KS *= 2) {
@@ -217,6 +217,14 @@ MfmaPlan plan_mfma(int ux, int wpx, int K, int nb, int mt_blocks, int m_tiles, b
 static MfmaPlan plan_for(int sched, int flags, int n_units, int K, int nb, int tile_m, int m_tiles, int n_xcd, int n_workers) {
   const bool split_ok = !(flags & FLEET_FLAG_NO_SPLITK) && (long)n_units * m_tiles <= GEMM_TILE_COUNTERS;
   const int wpx = n_workers / std::max(1, n_xcd);
+  // Small weight shares (one m-tile, at most RESIDENT_UNITS units per worker, K up to RESIDENT_K,
+  // not gate|up): every worker keeps its whole share in registers, requested before the wait, so
+  // the stage's HBM traffic overlaps the stage before it and nothing has to be reduced over workers.
+  {
+    const int ux = (n_units + n_xcd - 1) / std::max(1, n_xcd), g = (ux + std::max(1, wpx) - 1) / std::max(1, wpx);
+    if (!(flags & FLEET_FLAG_NO_RESIDENT) && nb == 1 && m_tiles == 1 && K <= RESIDENT_K && g <= RESIDENT_UNITS)
+      return MfmaPlan{g, 1, 1};
+  }
   if (msplit_applies(sched, P_MFMA, m_tiles, n_xcd)) {   // n_xcd / m_tiles XCDs share one m-tile and split N
     const int xpm = n_xcd / m_tiles;
     return plan_mfma((n_units + xpm - 1) / xpm, wpx, K, nb, mfma_blocks(tile_m), 1, split_ok);
@@ -276,7 +284,7 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   auto plan_bits = [&](int n_units, int K, int nb) {
     if (path != P_MFMA) return 0;
     const MfmaPlan pl = plan_for(s.sched_mode, s.flags, n_units, K, nb, tm, mt, n_xcd, n_workers);
-    return (pl.G << 12) | (pl.KS << 16);
+    return (pl.G << 12) | (pl.KS << 16) | (pl.resident << 21);
   };
 
   auto row_key = [](int i) { return i; };
@@ -392,13 +400,13 @@ Graph build_gemm_graph(int B, int K, int N, int sched_mode, int tile_m, int flag
   // Repetitions are independent unless FLEET_FLAG_CHAINED is set.  Split-K tiles count
   // their arrivals in one of two counter sets (bit 20 of aux2), so a repetition of such a
   // plan waits for the one before the previous: at most two are in flight.
-  MfmaPlan pl{1, 1};
+  MfmaPlan pl{1, 1, 0};
   if (path == P_MFMA) pl = plan_for(sched_mode, flags, N / ur, K, 1, tm, mt, n_xcd, n_workers);
   std::vector<int> evs;
   for (int r = 0; r < reps; ++r) {
     const int xm = path == P_FMA && (int64_t)B * K * 2 <= GEMV_LDS_X_BYTES && !(flags & FLEET_FLAG_SEPARATE_NORM)
                        ? X_LDS_COPY : X_GLOBAL;
-    const int bits = path == P_MFMA ? (pl.G << 12) | (pl.KS << 16) | ((r & 1) << 20) : 0;
+    const int bits = path == P_MFMA ? (pl.G << 12) | (pl.KS << 16) | ((r & 1) << 20) | (pl.resident << 21) : 0;
     int op = b.add_op(B_GEMM, r % std::max(1, n_copies), E_STORE_F32, path, K, N, ur, N / ur, mt, tm,
                       BUF_GEMM_X, BUF_GEMM_Y, 0, W_GEMM_COPY, (xm << 8) | (3 << 10) | bits);
     int wait = (flags & FLEET_FLAG_CHAINED) ? ev : (pl.KS > 1 && r >= 2) ? evs[r - 2] : -1;

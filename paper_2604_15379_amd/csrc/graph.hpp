@@ -69,7 +69,8 @@ enum {
 // bits 8..9 = activation mode of the FMA path (XMode), bits 10..11 = weight blocks the FMA
 // path requests before its dependency wait (0..3); MFMA path: bits 12..15 = units per tile,
 // bits 16..19 = k-slices of the split-K plan (1 = no split), bit 20 = counter set of the
-// split-K arrival counters (isolated GEMM repetitions alternate)
+// split-K arrival counters (isolated GEMM repetitions alternate), bit 21 = register-resident
+// weights (MfmaPlan::resident)
 enum XMode { X_GLOBAL = 0, X_LDS_COPY = 1, X_LDS_NORM = 2 };
 constexpr int GEMV_LDS_X_BYTES = 96 * 1024;   // LDS the FMA path may fill with activations
 // task word indices.  A0..A3 by body:
@@ -98,7 +99,10 @@ struct Graph {
 // Tile plan of an MFMA GEMM operator (units per tile, k-slices); a split-K plan needs one
 // arrival counter per (first unit of a tile, m-tile), GEMM_TILE_COUNTERS at most
 constexpr int GEMM_TILE_COUNTERS = 4096;
-struct MfmaPlan { int G, KS; };
+// resident = 1: the operator's weight share per worker (at most RESIDENT_UNITS units, K up to
+// RESIDENT_K) is held in registers whole, requested before the dependency wait; one k-slice
+constexpr int RESIDENT_UNITS = 2, RESIDENT_K = 4096;
+struct MfmaPlan { int G, KS, resident; };
 MfmaPlan plan_mfma(int units_per_xcd, int workers_per_xcd, int K, int nb, int mt_blocks, int m_tiles, bool allow_split);
 // 16-row blocks of batch rows the MFMA kernel for tile height tile_m accumulates (1, 2 or 4)
 int mfma_blocks(int tile_m);

@@ -143,6 +143,11 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
         gmax = max(1, (6 if blocks >= 4 or nb == 2 else 8) // nb)
         split_ok = not (flags & 32) and U * mt <= 4096
         wpx = max(1, n_workers // n_xcd)
+        # small weight shares stay in registers whole (bit 21): one m-tile, not gate|up, K up to
+        # 4096, at most 2 units per worker; G = units per worker, one k-slice
+        g_res = -(-(-(-U // n_xcd)) // wpx)
+        if not (flags & 128) and nb == 1 and mt == 1 and K <= 4096 and g_res <= 2:
+            return g_res << 12 | 1 << 16 | 1 << 21
         if msplit(mt):      # n_xcd / mt XCDs share one m-tile and split the units
             xpm = n_xcd // mt
             ux, tiles_m = -(-U // xpm), 1
@@ -272,7 +277,7 @@ CASES = [
 
 
 @pytest.mark.parametrize("sched,tile_m,flags", [(0, 0, 0), (0, 16, 0), (1, 0, 0), (1, 16, 0), (0, 0, 4), (1, 0, 4),
-                                                 (2, 16, 0), (2, 32, 0), (0, 16, 32), (1, 0, 32)])
+                                                 (2, 16, 0), (2, 32, 0), (0, 16, 32), (1, 0, 32), (0, 0, 128), (1, 0, 128)])
 def test_builder_equals_independent_derivation(sched, tile_m, flags):
     for sh, batches, n_xcd, n_workers in CASES:
         for b in batches:

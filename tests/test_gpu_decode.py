@@ -64,7 +64,8 @@ def test_fma_mfma_switch_moved_by_environment(monkeypatch, batch, fma_max):
                                                  (1, 0, F.FLAG_SEPARATE_NORM),
                                                  (F.SCHED_MSPLIT, 16, 0), (F.SCHED_MSPLIT, 0, 0),
                                                  (0, 0, F.FLAG_NO_SPLITK), (1, 16, F.FLAG_NO_SPLITK),
-                                                 (0, 0, F.FLAG_NO_STREAM)])
+                                                 (0, 0, F.FLAG_NO_STREAM), (0, 0, F.FLAG_NO_RESIDENT),
+                                                 (1, 0, F.FLAG_NO_RESIDENT)])
 @pytest.mark.parametrize("batch", [3, 40])
 def test_schedules_agree_with_oracle(batch, sched, tile_m, flags):
     print(f"decode modes batch={batch} sched={sched} tile_m={tile_m} flags={flags}", flush=True)

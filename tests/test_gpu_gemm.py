@@ -43,7 +43,8 @@ def test_gemm_small_shapes(B, K, N):
 @pytest.mark.parametrize("sched,tile_m,flags", [(0, 16, 0), (1, 16, 0), (1, 0, 0), (0, 32, 0),
                                                  (0, 16, F.FLAG_SINGLE_LEVEL), (0, 0, F.FLAG_CHAINED),
                                                  (0, 0, F.FLAG_SEPARATE_NORM), (F.SCHED_MSPLIT, 16, 0),
-                                                 (0, 0, F.FLAG_NO_SPLITK), (0, 0, F.FLAG_NO_STREAM)])
+                                                 (0, 0, F.FLAG_NO_SPLITK), (0, 0, F.FLAG_NO_STREAM),
+                                                 (0, 0, F.FLAG_NO_RESIDENT)])
 @pytest.mark.parametrize("B", [4, 48])
 def test_gemm_schedules_and_tiles(B, sched, tile_m, flags):
     print(f"gemm modes B={B} sched={sched} tile_m={tile_m} flags={flags}", flush=True)
