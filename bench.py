@@ -203,7 +203,7 @@ def main():
                      "frac": gbps / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes": step_bytes,
                      "kernel": "fleet_persistent_kernel (one launch per step)"},
-        "l2_hit_model": F.fleet_l2_hit_model(B, a.tile_m or 16 * ((B + 15) // 16) if B > 4 else B or 1, 32),
+        "l2_hit_model": F.fleet_l2_hit_model(B, a.tile_m or 16 * ((B + 15) // 16) if B > 2 else B or 1, 32),
         "workers_per_xcd": st["workers"],
     }
     if not a.no_cpu_baseline:

@@ -78,7 +78,7 @@ typedef struct {
   int32_t sched_mode; /* enum fleet_sched                                                */
   int32_t tile_m;     /* GEMM tile height along the batch on the MFMA path: 16, 32, 64, or
                          0 = whole batch rounded up to 16 (reads each weight once).
-                         Batches up to 4 run FMA GEMV kernels, larger ones bf16 MFMA
+                         Batches up to 2 run FMA GEMV kernels, larger ones bf16 MFMA
                          kernels; the environment variable FLEET_FMA_MAX_BATCH (0..8),
                          read when a graph is built, moves that switch                  */
   int32_t flags;      /* enum fleet_flags                                                */

@@ -81,7 +81,7 @@ INGEST, RMSNORM, GEMM, ATTN, FINAL = 0, 1, 2, 3, 5
 LDS_X_BYTES = 96 * 1024      # activations the FMA path may keep in LDS
 
 
-FMA_MAX = 4   # largest batch on the FMA GEMV path (FLEET_FMA_MAX_BATCH unset)
+FMA_MAX = 2   # largest batch on the FMA GEMV path (FLEET_FMA_MAX_BATCH unset)
 
 
 def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0):
@@ -270,8 +270,8 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
 
 
 CASES = [
-    (si.reduced_shape(max_batch=64, n_layers=2, vocab=2064), [1, 5, 8, 9, 33, 64], 8, 256),
-    (si.qwen3_8b_shape(64, 4097, n_layers=3), [1, 8, 32, 64], 8, 256),
+    (si.reduced_shape(max_batch=64, n_layers=2, vocab=2064), [1, 2, 5, 8, 9, 33, 64], 8, 256),
+    (si.qwen3_8b_shape(64, 4097, n_layers=3), [1, 2, 8, 32, 64], 8, 256),
     (si.reduced_shape(max_batch=4), [1, 3], 4, 120),          # another chiplet count / CU count
 ]
 

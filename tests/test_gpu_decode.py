@@ -39,10 +39,10 @@ def test_two_layers_ragged_positions_with_lm_head(batch):
     check_new_kv(m, got[2], got[3], k, v)
 
 
-@pytest.mark.parametrize("batch,fma_max", [(5, 8), (8, 8), (3, 1), (4, 0)])
+@pytest.mark.parametrize("batch,fma_max", [(5, 8), (8, 8), (4, 4), (3, 4), (2, 1), (1, 0)])
 def test_fma_mfma_switch_moved_by_environment(monkeypatch, batch, fma_max):
     """FLEET_FMA_MAX_BATCH moves the batch at which the GEMMs switch from the FMA GEMV kernels
-    to the MFMA kernels: batch 5 and 8 on the FMA kernels, batch 3 and 4 on the MFMA ones."""
+    to the MFMA kernels: batch 3 to 8 on the FMA kernels, batch 1 and 2 on the MFMA ones."""
     monkeypatch.setenv("FLEET_FMA_MAX_BATCH", str(fma_max))
     print(f"decode 2 layers batch={batch} FLEET_FMA_MAX_BATCH={fma_max}", flush=True)
     sh = si.reduced_shape(max_batch=batch, max_seq=160, n_layers=2, vocab=1024)
