@@ -63,9 +63,12 @@ enum fleet_flags {
   FLEET_FLAG_NO_SPLITK = 32,   /* MFMA GEMMs: never split K over workers (one k-slice)  */
   FLEET_FLAG_NO_STREAM = 64,   /* weight loads without the non-temporal (streaming)
                                   cache hint (section 3.2, cache-modifier flavours)     */
-  FLEET_FLAG_NO_RESIDENT = 128 /* MFMA GEMMs: never hold a worker's whole weight share in
+  FLEET_FLAG_NO_RESIDENT = 128,/* MFMA GEMMs: never hold a worker's whole weight share in
                                   registers across the dependency wait (small GEMMs then
                                   use split-K tiles)                                    */
+  FLEET_FLAG_UNFUSED_SILU = 256/* gate|up GEMM stores its fp32 sums; SiLU(gate) x up runs as
+                                  a stage of CU-tasks of its own (section 3.2, operator
+                                  fusion ablation)                                      */
 };
 
 typedef struct {

@@ -185,7 +185,7 @@ struct fleet {
   DevInfo info;
   // scratch activations (device)
   float* x = nullptr; void* n = nullptr; float* qkv = nullptr; void* att = nullptr; void* h = nullptr;
-  float* part = nullptr; float* gpart = nullptr; float2* rope = nullptr;
+  float* part = nullptr; float* gpart = nullptr; float* gu32 = nullptr; float2* rope = nullptr;
   int32_t* status = nullptr; int32_t* trace = nullptr;
   std::map<int, std::unique_ptr<DevGraph>> graphs;
   long long timeout_ticks = 0;
@@ -315,7 +315,7 @@ int run_layers(fleet* f, int batch, int layer_begin, int layer_end, bool with_in
   memset(&P, 0, sizeof(P));
   fill_graph_params(P, dg);
   P.buf[BUF_X] = f->x; P.buf[BUF_N] = f->n; P.buf[BUF_QKV] = f->qkv; P.buf[BUF_ATT] = f->att; P.buf[BUF_H] = f->h;
-  P.buf[BUF_PART] = f->part; P.buf[BUF_GPART] = f->gpart; P.buf[BUF_HIDDEN_IN] = (void*)hidden_in; P.buf[BUF_TOKENS] = (void*)tokens;
+  P.buf[BUF_PART] = f->part; P.buf[BUF_GPART] = f->gpart; P.buf[BUF_GU32] = f->gu32; P.buf[BUF_HIDDEN_IN] = (void*)hidden_in; P.buf[BUF_TOKENS] = (void*)tokens;
   P.buf[BUF_KC] = k_cache; P.buf[BUF_VC] = v_cache; P.buf[BUF_POS] = (void*)positions;
   P.buf[BUF_HIDDEN_OUT] = hidden_out; P.buf[BUF_LOGITS] = logits;
   P.status = f->status; P.trace = (f->shape.flags & (FLEET_FLAG_TRACE | FLEET_FLAG_TIMING)) ? f->trace : nullptr; P.trace_cap = TRACE_CAP;
@@ -414,6 +414,8 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
     if (shape->vocab > 0 && (size_t)shape->vocab / 16 * 4 <= (size_t)GEMM_TILE_COUNTERS) nmax = std::max(nmax, (size_t)shape->vocab);
     if ((rc = upload(&f->gpart, nullptr, 8 * 64 * nmax * 4))) return rc;
   }
+  if (shape->flags & FLEET_FLAG_UNFUSED_SILU)   // fp32 [gate | up] sums of the unfused gate|up GEMM
+    if ((rc = upload(&f->gu32, nullptr, mb * 2 * F * 4))) return rc;
   if ((rc = upload(&f->status, nullptr, dev::ST_WORDS * 4))) return rc;
   HIP_TRY(hipMemset(f->status, 0, dev::ST_WORDS * 4));
   if (shape->flags & (FLEET_FLAG_TRACE | FLEET_FLAG_TIMING))
@@ -438,7 +440,7 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
 int fleet_destroy(fleet_t* f) {
   if (!f) return FLEET_OK;
   (void)hipDeviceSynchronize();
-  for (void* p : {(void*)f->x, f->n, (void*)f->qkv, f->att, f->h, (void*)f->part, (void*)f->gpart, (void*)f->rope, (void*)f->status, (void*)f->trace})
+  for (void* p : {(void*)f->x, f->n, (void*)f->qkv, f->att, f->h, (void*)f->part, (void*)f->gpart, (void*)f->gu32, (void*)f->rope, (void*)f->status, (void*)f->trace})
     if (p) (void)hipFree(p);
   for (auto* v : {&f->pk_qkv, &f->pk_o, &f->pk_gu, &f->pk_down})
     for (void* p : *v) if (p) (void)hipFree(p);

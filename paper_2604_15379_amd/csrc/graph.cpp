@@ -356,17 +356,27 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
 
     // gate | up rows of one concatenated matrix; a unit is ur gate rows plus the
     // matching ur up rows (aux = row offset of the up half), SwiGLU in the epilogue
+    // FLEET_FLAG_UNFUSED_SILU: a plain GEMM over all 2 * ffn rows stores fp32 sums, and a
+    // stage of CU-tasks (one per sequence) applies SiLU(gate) x up afterwards.
+    const bool unfused = (s.flags & FLEET_FLAG_UNFUSED_SILU) != 0;
+    const Epi gu_epi = unfused ? E_STORE_F32 : E_SWIGLU_BF16;
+    const int gu_n = unfused ? 2 * F : F, gu_aux = unfused ? 0 : F, gu_nb = unfused ? 1 : 2;
+    const Buf gu_out = unfused ? BUF_GU32 : BUF_H;
     int op_gu;
     if (fuse_norm) {
-      op_gu = b.add_op(B_GEMM, l, E_SWIGLU_BF16, path, H, F, ur, F / ur, mt, tm, BUF_X, BUF_H, F, W_GU,
+      op_gu = b.add_op(B_GEMM, l, gu_epi, path, H, gu_n, ur, gu_n / ur, mt, tm, BUF_X, gu_out, gu_aux, W_GU,
                        W_LN2 | (X_LDS_NORM << 8) | PRE2);
     } else {
       int op_n2 = b.add_op(B_RMSNORM, l, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N, 0, W_LN2);
       ev = b.cu_stage(op_n2, batch, ev, row_key, row_arg);
-      op_gu = b.add_op(B_GEMM, l, E_SWIGLU_BF16, path, H, F, ur, F / ur, mt, tm, BUF_N, BUF_H, F, W_GU,
-                       (xmode(H) << 8) | PRE2 | plan_bits(F / ur, H, 2));
+      op_gu = b.add_op(B_GEMM, l, gu_epi, path, H, gu_n, ur, gu_n / ur, mt, tm, BUF_N, gu_out, gu_aux, W_GU,
+                       (xmode(H) << 8) | PRE2 | plan_bits(gu_n / ur, H, gu_nb));
     }
     ev = b.gemm_stage(op_gu, ev);
+    if (unfused) {
+      int op_sw = b.add_op(B_SWIGLU, l, E_SWIGLU_BF16, P_FMA, F, F, 0, 0, 1, batch, BUF_GU32, BUF_H, F, W_NONE);
+      ev = b.cu_stage(op_sw, batch, ev, row_key, row_arg);
+    }
 
     int op_dn = b.add_op(B_GEMM, l, E_RESID_F32, path, F, H, ur, H / ur, mt, tm, BUF_H, BUF_X, 0, W_DOWN,
                       (xmode(F) << 8) | PRE2 | plan_bits(H / ur, F, 1));

@@ -75,9 +75,9 @@ def test_step_bytes_accounting():
 
 # ------------------------------------------------------------------ graph re-derivation
 BUF = dict(NONE=0, X=1, N=2, QKV=3, ATT=4, H=5, PART=6, HIDDEN_IN=7, TOKENS=8, KC=9, VC=10, POS=11,
-           HIDDEN_OUT=12, LOGITS=13)
+           HIDDEN_OUT=12, LOGITS=13, GEMM_X=14, GEMM_Y=15, GPART=16, GU32=17)
 WK = dict(NONE=0, QKV=1, O=2, GU=3, DOWN=4, LM=5, LN1=6, LN2=7, FINAL=8, EMBED=9)
-INGEST, RMSNORM, GEMM, ATTN, FINAL = 0, 1, 2, 3, 5
+INGEST, RMSNORM, GEMM, ATTN, SWIGLU, FINAL = 0, 1, 2, 3, 4, 5
 LDS_X_BYTES = 96 * 1024      # activations the FMA path may keep in LDS
 
 
@@ -243,14 +243,21 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
         ev = gemm_stage(op(GEMM, l, 1, path, QD, H, ur, H // ur, mt, tm, BUF["ATT"], BUF["X"], Fd if warm else 0,
                            WK["O"], (WK["GU"] if warm else 0) | xm(QD) | plan(H // ur, QD, 1)), ev,
                         o_skip if fma else None)
+        # flag 256 (unfused SiLU): a plain GEMM over all 2 * ffn rows stores fp32 sums and a stage
+        # of CU-tasks, one per sequence, applies SiLU(gate) x up
+        unfused = bool(flags & 256)
+        epi, gn, gaux, gnb = (0, 2 * Fd, 0, 1) if unfused else (2, Fd, Fd, 2)
+        gout = BUF["GU32"] if unfused else BUF["H"]
         if fuse:
-            o_gu = op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["X"], BUF["H"], Fd, WK["GU"],
+            o_gu = op(GEMM, l, epi, path, H, gn, ur, gn // ur, mt, tm, BUF["X"], gout, gaux, WK["GU"],
                       WK["LN2"] | 2 << 8 | PRE)
         else:
             ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN2"]), rows, ev)
-            o_gu = op(GEMM, l, 2, path, H, Fd, ur, Fd // ur, mt, tm, BUF["N"], BUF["H"], Fd, WK["GU"],
-                      xm(H) | plan(Fd // ur, H, 2))
+            o_gu = op(GEMM, l, epi, path, H, gn, ur, gn // ur, mt, tm, BUF["N"], gout, gaux, WK["GU"],
+                      xm(H) | plan(gn // ur, H, gnb))
         ev = gemm_stage(o_gu, ev)
+        if unfused:
+            ev = cu_stage(op(SWIGLU, l, 2, 0, Fd, Fd, 0, 0, 1, batch, BUF["GU32"], BUF["H"], Fd, WK["NONE"]), rows, ev)
         ev = gemm_stage(op(GEMM, l, 1, path, Fd, H, ur, H // ur, mt, tm, BUF["H"], BUF["X"], 0, WK["DOWN"],
                            xm(Fd) | plan(H // ur, Fd, 1)), ev)
         xready.append(ev)
@@ -277,7 +284,8 @@ CASES = [
 
 
 @pytest.mark.parametrize("sched,tile_m,flags", [(0, 0, 0), (0, 16, 0), (1, 0, 0), (1, 16, 0), (0, 0, 4), (1, 0, 4),
-                                                 (2, 16, 0), (2, 32, 0), (0, 16, 32), (1, 0, 32), (0, 0, 128), (1, 0, 128)])
+                                                 (2, 16, 0), (2, 32, 0), (0, 16, 32), (1, 0, 32), (0, 0, 128), (1, 0, 128),
+                                                 (0, 0, 256), (1, 16, 256)])
 def test_builder_equals_independent_derivation(sched, tile_m, flags):
     for sh, batches, n_xcd, n_workers in CASES:
         for b in batches:
