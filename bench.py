@@ -63,6 +63,9 @@ def parse():
                     help="isolated skinny-GEMM sweep at the Qwen3-8B shapes (one JSON line per case)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="run only a plain copy of this many MiB (counter calibration under rocprofv3)")
+    ap.add_argument("--tokens-per-launch", type=int, default=0, metavar="T",
+                    help="time T greedy decode steps per launch of the persistent kernel (fleet_decode_tokens) "
+                         "instead of one step per launch; one JSON line")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per step from rocprofv3 counters (reported as roofline.traffic)")
     return ap.parse_args()
@@ -124,6 +127,61 @@ def gemm_sweep(a):
         del ws
 
 
+def tokens_per_launch(a):
+    """T greedy steps in one launch (the kernel stays resident over the tokens) against the
+    same T steps launched one by one from the host; positions start at --kv and advance."""
+    import numpy as np
+    import torch
+    import paper_2604_15379_amd as F
+    import synth_inputs as si
+    B, T = a.batch, a.tokens_per_launch
+    shape = si.qwen3_8b_shape(max_batch=B, max_seq=a.kv + T + 1, n_layers=a.layers)
+    g = si.Gen(a.seed, "cuda")
+    w = si.make_weights(shape, g, with_embed=True)
+    kc, vc = si.make_kv_cache(shape, g)
+    tok0 = g.randint(0, shape.vocab - 1, B).to(torch.int32)
+    hout = torch.empty((B, shape.hidden), device="cuda", dtype=torch.float32)
+    logits = torch.empty((B, shape.vocab), device="cuda", dtype=torch.float32)
+    out = torch.empty((T, B), device="cuda", dtype=torch.int32)
+    f = F.fleet_create(shape.asdict(), w, a.sched, a.tile_m, a.flags)
+    stream = torch.cuda.current_stream().cuda_stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def one_launch():
+        tok, pos = tok0.clone(), torch.full((B,), a.kv, device="cuda", dtype=torch.int32)
+        torch.cuda.synchronize()
+        e0.record()
+        F.fleet_decode_tokens(f, B, tok, kc, vc, pos, T, out, hout, logits, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    def host_loop():
+        tok, pos = tok0.clone(), torch.full((B,), a.kv, device="cuda", dtype=torch.int32)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(T):   # the host chooses the token (device-side argmax, no host sync)
+            F.fleet_decode_step(f, B, None, tok, kc, vc, pos, hout, logits, stream)
+            tok = logits.argmax(dim=1).to(torch.int32)
+            pos += 1
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    one_launch(); host_loop()
+    ms_launch = min(one_launch() for _ in range(max(1, a.steps // T)))
+    st = F.fleet_last_status(f)
+    if st["code"] != 0:
+        raise SystemExit(f"decode failed: {st}")
+    ms_host = min(host_loop() for _ in range(max(1, a.steps // T)))
+    F.fleet_destroy(f)
+    print(json.dumps({"metric": "decode_step_latency_us", "value": ms_launch * 1e3 / T, "unit": "us", "n_gpus": 1,
+                      "config": {"workload": f"Qwen3-8B-shaped greedy decoding, {a.layers} layers + LM head, batch {B}, "
+                                             f"KV {a.kv}.., {T} steps per launch of the persistent kernel",
+                                 "batch": B, "tokens_per_launch": T},
+                      "one_step_per_launch_us": ms_host * 1e3 / T, "tokens_per_s": B * T / (ms_launch * 1e-3)}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -148,6 +206,9 @@ def main():
         return
     if a.gemm_sweep:
         gemm_sweep(a)
+        return
+    if a.tokens_per_launch > 0:
+        tokens_per_launch(a)
         return
     B = a.batch
     shape = si.qwen3_8b_shape(max_batch=B, max_seq=a.kv + 1, n_layers=a.layers)

@@ -167,6 +167,26 @@ int fleet_decode_layers(fleet_t *f, int32_t batch, int32_t layer_begin, int32_t 
 int fleet_destroy(fleet_t *f);
 
 /*
+ * fleet_decode_tokens: n_tokens greedy decode steps in ONE launch of the persistent kernel
+ * (paper section 4.1: the kernel stays resident over the generated tokens; no return to the
+ * host between steps).  Each step gathers embed[tokens[b]], runs the decoder stack and the LM
+ * head as fleet_decode_step does, and a last stage of CU-tasks takes, per sequence, the index
+ * of the largest logit (the lowest index among equal ones) as the next token.
+ *   tokens     device int32 [batch], in/out: the input token of the first step; on return
+ *              the last token generated
+ *   positions  device int32 [batch], in/out: advanced by one per step (positions[b] +
+ *              n_tokens <= max_seq, else the launch aborts with FLEET_EINVAL in the status)
+ *   tokens_out device int32 [n_tokens, batch]: the token chosen in every step
+ *   hidden_out device fp32 [batch, hidden], logits device fp32 [batch, vocab]: workspace
+ *              and result of the last step
+ * Needs embed, final_norm and lm_head.  Asynchronous on `stream`; fleet_last_status
+ * reports a time-out or a bad position.  No trace is recorded for such a launch.
+ */
+int fleet_decode_tokens(fleet_t *f, int32_t batch, int32_t *tokens, void *k_cache, void *v_cache,
+                        int32_t *positions, int32_t n_tokens, int32_t *tokens_out,
+                        float *hidden_out, float *logits, void *stream);
+
+/*
  * fleet_gemm (test / measurement): y = x . W^T as `reps` back-to-back device-tasks
  * of the persistent kernel, the GEMM of paper section 3.2 in isolation.
  *   x         device bf16 [B, K]

@@ -20,7 +20,8 @@ FLAG_TRACE, FLAG_SINGLE_LEVEL, FLAG_SEPARATE_NORM, FLAG_CHAINED, FLAG_TIMING = 1
 FLAG_NO_SPLITK, FLAG_NO_STREAM, FLAG_NO_RESIDENT, FLAG_UNFUSED_SILU = 32, 64, 128, 256
 
 EXPORTS = (
-    "fleet_create", "fleet_decode_step", "fleet_decode_layers", "fleet_destroy", "fleet_gemm",
+    "fleet_create", "fleet_decode_step", "fleet_decode_layers", "fleet_decode_tokens", "fleet_destroy",
+    "fleet_gemm",
     "fleet_graph_build", "fleet_graph_dump", "fleet_trace_read", "fleet_last_status",
     "fleet_device_probe", "fleet_copy", "fleet_weight_bytes", "fleet_weight_bytes_per_xcd",
     "fleet_l2_window_bytes", "fleet_l2_hit_model", "fleet_effective_intensity",
@@ -147,6 +148,16 @@ def fleet_decode_layers(f: Fleet, batch: int, layer_begin: int, layer_end: int, 
                                             _ptr(logits), C.c_void_p(stream))
     if rc != 0:
         raise FleetError(rc, "fleet_decode_layers")
+
+
+def fleet_decode_tokens(f: Fleet, batch: int, tokens, k_cache, v_cache, positions, n_tokens: int,
+                        tokens_out, hidden_out, logits, stream=0) -> None:
+    rc = load_library().fleet_decode_tokens(f.handle, C.c_int32(batch), _ptr(tokens), _ptr(k_cache),
+                                            _ptr(v_cache), _ptr(positions), C.c_int32(n_tokens),
+                                            _ptr(tokens_out), _ptr(hidden_out), _ptr(logits),
+                                            C.c_void_p(stream))
+    if rc != 0:
+        raise FleetError(rc, "fleet_decode_tokens")
 
 
 def fleet_destroy(f: Fleet) -> None:

@@ -187,7 +187,8 @@ struct fleet {
   float* x = nullptr; void* n = nullptr; float* qkv = nullptr; void* att = nullptr; void* h = nullptr;
   float* part = nullptr; float* gpart = nullptr; float* gu32 = nullptr; float2* rope = nullptr;
   int32_t* status = nullptr; int32_t* trace = nullptr;
-  std::map<int, std::unique_ptr<DevGraph>> graphs;
+  std::map<int, std::unique_ptr<DevGraph>> graphs;        // by batch size
+  std::map<int, std::unique_ptr<DevGraph>> graphs_loop;   // with the next-token stage (multi-step launches)
   long long timeout_ticks = 0;
   int last_code = 0;
   DevGraph* last_graph = nullptr;
@@ -290,24 +291,25 @@ void fill_graph_params(dev::Params& P, const DevGraph* dg) {
   P.fat = dg->fat; P.ctr = dg->ctr; P.n_events = dg->g.n_events(); P.gcnt_base = dg->gcnt_base;
 }
 
-int get_graph(fleet* f, int batch, DevGraph** out) {
-  auto it = f->graphs.find(batch);
-  if (it != f->graphs.end()) { *out = it->second.get(); return FLEET_OK; }
+int get_graph(fleet* f, int batch, DevGraph** out, bool loop = false) {
+  auto& cache = loop ? f->graphs_loop : f->graphs;
+  auto it = cache.find(batch);
+  if (it != cache.end()) { *out = it->second.get(); return FLEET_OK; }
   std::unique_ptr<DevGraph> dg(new (std::nothrow) DevGraph());
   if (!dg) return FLEET_ENOMEM;
-  dg->g = build_decode_graph(f->shape, batch, f->info.n_xcd, f->info.n_cu);
+  dg->g = build_decode_graph(f->shape, batch, f->info.n_xcd, f->info.n_cu, loop);
   int rc = upload_graph(dg.get(), f, nullptr, f->info.n_xcd);
   if (rc) return rc;
   *out = dg.get();
-  f->graphs[batch] = std::move(dg);
+  cache[batch] = std::move(dg);
   return FLEET_OK;
 }
-
+// n_tokens > 0: the whole step n_tokens times in one launch (graph with the next-token stage)
 int run_layers(fleet* f, int batch, int layer_begin, int layer_end, bool with_ingest, bool with_final,
                const void* hidden_in, const int32_t* tokens, void* k_cache, void* v_cache, const int32_t* positions,
-               float* hidden_out, float* logits, hipStream_t st) {
+               float* hidden_out, float* logits, hipStream_t st, int n_tokens = 0, int32_t* tokens_out = nullptr) {
   DevGraph* dg = nullptr;
-  int rc = get_graph(f, batch, &dg);
+  int rc = get_graph(f, batch, &dg, n_tokens > 0);
   if (rc) return rc;
   const Graph& g = dg->g;
   const int L = f->shape.n_layers, n_marks = L + 3, nx = f->info.n_xcd;
@@ -317,8 +319,11 @@ int run_layers(fleet* f, int batch, int layer_begin, int layer_end, bool with_in
   P.buf[BUF_X] = f->x; P.buf[BUF_N] = f->n; P.buf[BUF_QKV] = f->qkv; P.buf[BUF_ATT] = f->att; P.buf[BUF_H] = f->h;
   P.buf[BUF_PART] = f->part; P.buf[BUF_GPART] = f->gpart; P.buf[BUF_GU32] = f->gu32; P.buf[BUF_HIDDEN_IN] = (void*)hidden_in; P.buf[BUF_TOKENS] = (void*)tokens;
   P.buf[BUF_KC] = k_cache; P.buf[BUF_VC] = v_cache; P.buf[BUF_POS] = (void*)positions;
-  P.buf[BUF_HIDDEN_OUT] = hidden_out; P.buf[BUF_LOGITS] = logits;
-  P.status = f->status; P.trace = (f->shape.flags & (FLEET_FLAG_TRACE | FLEET_FLAG_TIMING)) ? f->trace : nullptr; P.trace_cap = TRACE_CAP;
+  P.buf[BUF_HIDDEN_OUT] = hidden_out; P.buf[BUF_LOGITS] = logits; P.buf[BUF_TOKENS_OUT] = tokens_out;
+  P.n_iter = n_tokens > 0 ? n_tokens : 1;
+  P.status = f->status; P.trace_cap = TRACE_CAP;
+  // (no trace of a multi-step launch: the record area holds one step)
+  P.trace = (n_tokens == 0 && (f->shape.flags & (FLEET_FLAG_TRACE | FLEET_FLAG_TIMING))) ? f->trace : nullptr;
   P.rope = f->rope; P.timeout_ticks = f->timeout_ticks; P.n_xcd = nx; P.flags = f->shape.flags;
   P.nq = f->shape.n_q_heads; P.nkv = f->shape.n_kv_heads; P.hd = f->shape.head_dim; P.max_batch = f->shape.max_batch;
   P.max_seq = f->shape.max_seq; P.hidden = f->shape.hidden; P.ffn = f->shape.ffn; P.batch = batch; P.eps = f->shape.rms_eps; P.vocab = f->shape.vocab;
@@ -478,6 +483,16 @@ int fleet_decode_layers(fleet_t* f, int32_t batch, int32_t layer_begin, int32_t 
   return FLEET_OK;
 }
 
+int fleet_decode_tokens(fleet_t* f, int32_t batch, int32_t* tokens, void* k_cache, void* v_cache, int32_t* positions,
+                        int32_t n_tokens, int32_t* tokens_out, float* hidden_out, float* logits, void* stream) {
+  if (!f || batch < 1 || batch > f->shape.max_batch || !tokens || !k_cache || !v_cache || !positions || !tokens_out ||
+      !hidden_out || !logits || n_tokens < 1 || n_tokens > 65536)
+    return FLEET_EINVAL;
+  if (f->shape.vocab <= 0 || !f->embed || !f->lm_head || !f->final_norm) return FLEET_EINVAL;
+  return run_layers(f, batch, 0, f->shape.n_layers, true, true, nullptr, tokens, k_cache, v_cache, positions, hidden_out,
+                    logits, (hipStream_t)stream, n_tokens, tokens_out);
+}
+
 int fleet_last_status(fleet_t* f, fleet_status_t* out) {
   if (!f || !out) return FLEET_EINVAL;
   memset(out, 0, sizeof(*out));
@@ -578,6 +593,7 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const
   memset(&P, 0, sizeof(P));
   fill_graph_params(P, &dg);
   P.buf[BUF_GEMM_X] = mfma ? xp : (void*)x; P.buf[BUF_GEMM_Y] = y; P.buf[BUF_GPART] = gpart;
+  P.n_iter = 1;
   P.status = status; P.timeout_ticks = timeout_ticks_from_env(); P.n_xcd = info.n_xcd; P.flags = flags;
   P.batch = B; P.hidden = K;
   for (int xc = 0; xc < info.n_xcd; ++xc) { P.q_begin[xc] = dg.g.marks[(size_t)xc * 3 + 0]; P.q_end[xc] = dg.g.marks[(size_t)xc * 3 + 2]; }

@@ -271,7 +271,7 @@ int check_shape(const fleet_shape_t& s) {
   return FLEET_OK;
 }
 
-Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_workers) {
+Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_workers, bool loop) {
   Builder b(n_xcd, n_workers, s.sched_mode, batch);
   const int H = s.hidden, hd = s.head_dim, nq = s.n_q_heads, nkv = s.n_kv_heads, F = s.ffn;
   const int QD = nq * hd, NQKV = (nq + 2 * nkv) * hd;
@@ -393,6 +393,10 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
     int op_lm = b.add_op(B_GEMM, -1, E_STORE_F32, path, H, s.vocab, ur, s.vocab / ur, mt, tm, BUF_N,
                          BUF_LOGITS, 0, W_LM, (xmode(H) << 8) | PRE2 | plan_bits(s.vocab / ur, H, 1));
     ev = b.gemm_stage(op_lm, ev);
+    if (loop) {   // greedy next token per sequence; its event is the graph's last
+      int op_am = b.add_op(B_ARGMAX, -1, E_STORE_F32, P_FMA, s.vocab, s.vocab, 0, 0, 1, batch, BUF_LOGITS, BUF_TOKENS, 0, W_NONE);
+      ev = b.cu_stage(op_am, batch, ev, row_key, row_arg);
+    }
   }
   b.mark_all();
   return b.finish(s.n_layers, tm, path, S, mt);

@@ -35,7 +35,7 @@ enum {
   H_BATCH, H_SCHED, H_TILE_M, H_PATH, H_N_SPLITS, H_N_WORKERS, H_M_TILES, H_TOTAL_WORDS
 };
 
-enum Body { B_INGEST = 0, B_RMSNORM = 1, B_GEMM = 2, B_ATTN = 3, B_SWIGLU = 4, B_FINAL = 5 };
+enum Body { B_INGEST = 0, B_RMSNORM = 1, B_GEMM = 2, B_ATTN = 3, B_SWIGLU = 4, B_FINAL = 5, B_ARGMAX = 6 };
 enum Epi { E_STORE_F32 = 0, E_RESID_F32 = 1, E_SWIGLU_BF16 = 2 };
 enum Path { P_FMA = 0, P_MFMA = 1 };
 enum Scope { S_WAVE = 0, S_CU = 1, S_CHIPLET = 2 };
@@ -50,7 +50,7 @@ constexpr int ATTN_TWO_LEVEL_MIN_PER_XCD = 8;
 // activation / caller buffers, resolved to pointers per step
 enum Buf {
   BUF_NONE = 0, BUF_X, BUF_N, BUF_QKV, BUF_ATT, BUF_H, BUF_PART, BUF_HIDDEN_IN, BUF_TOKENS,
-  BUF_KC, BUF_VC, BUF_POS, BUF_HIDDEN_OUT, BUF_LOGITS, BUF_GEMM_X, BUF_GEMM_Y, BUF_GPART, BUF_GU32, N_BUF
+  BUF_KC, BUF_VC, BUF_POS, BUF_HIDDEN_OUT, BUF_LOGITS, BUF_GEMM_X, BUF_GEMM_Y, BUF_GPART, BUF_GU32, BUF_TOKENS_OUT, N_BUF
 };
 
 // which caller weight an op reads (resolved with the op's layer)
@@ -79,7 +79,7 @@ constexpr int GEMV_LDS_X_BYTES = 96 * 1024;   // LDS the FMA path may fill with 
 //                       only (M-split), else 0                 (tiles = units x m_tiles)
 //   GEMM CU-task      : A0 first unit, A1 unit count, A2 m-tile, A3 k-slice
 //   ATTN              : A0 batch row, A1 kv head, A2 split, A3 n_splits
-//   INGEST/RMSNORM/SWIGLU/FINAL : A0 batch row
+//   INGEST/RMSNORM/SWIGLU/FINAL/ARGMAX : A0 batch row
 enum { T_OP = 0, T_SCOPE, T_XCD, T_A0, T_A1, T_A2, T_A3, T_WAIT_EVENT, T_SIGNAL_EVENT, T_STAGE };
 // event word indices: threshold counts device-level signals (XCDs for a
 // two-level event, tasks for a direct one); n_tasks counts the signalling tasks
@@ -116,7 +116,9 @@ int attention_splits(int batch, int n_kv_heads, int n_workers, int max_seq);
 int check_shape(const fleet_shape_t& s);
 
 // the decode-step graph for `batch` sequences on n_xcd chiplets, n_workers workgroups
-Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_workers);
+// loop = true: a last stage of ARGMAX CU-tasks (greedy next token, one per sequence) so that a
+// launch can run several decode steps back to back
+Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_workers, bool loop = false);
 // `reps` GEMM device-tasks y = x W^T (rep i reads weight copy i % n_copies)
 Graph build_gemm_graph(int B, int K, int N, int sched_mode, int tile_m, int flags, int reps,
                        int n_copies, int n_xcd, int n_workers);

@@ -6,7 +6,7 @@ import torch
 import oracle
 import paper_2604_15379_amd as F
 import synth_inputs as si
-from gpu_common import Model, assert_close, check_new_kv, TOL
+from gpu_common import Model, assert_close, check_new_kv, rms, TOL
 
 pytestmark = pytest.mark.gpu
 
@@ -88,6 +88,58 @@ def test_embedding_gather_input():
     got = m.run_gpu(tokens=tok)
     assert_close(got[0], ho, "hidden_out")
     assert_close(got[1], lg, "logits")
+
+
+@pytest.mark.parametrize("batch,sched", [(1, 0), (2, 0), (2, 1), (5, 0), (5, 1), (20, 0)])
+def test_greedy_tokens_in_one_launch(batch, sched):
+    """fleet_decode_tokens: several greedy steps in one launch of the persistent kernel equal
+    the oracle stepped from the host (embedding gather, decode step, first index of the largest
+    logit, position + 1).  Where the oracle's two best logits are closer than the tolerance on
+    logits either may win; the comparison then ends (the sequences continue differently)."""
+    n_tokens = 6
+    print(f"greedy tokens batch={batch} sched={sched}", flush=True)
+    sh = si.reduced_shape(max_batch=batch, max_seq=64, n_layers=2, vocab=1024)
+    pos0 = np.random.default_rng(batch).integers(0, 64 - n_tokens, batch).astype(np.int32)
+    m = Model(sh, seed=30 + batch, batch=batch, positions=pos0, with_embed=True)
+    tok0 = np.random.default_rng(99).integers(0, sh.vocab, batch).astype(np.int32)
+    # oracle, one step per call
+    k, v = m.host_caches()
+    tok, pos = tok0.copy(), pos0.copy()
+    ref_tokens, margins, lg = [], [], None
+    for _ in range(n_tokens):
+        _, lg = oracle.decode_step(sh.asdict(), m.w_host, batch, pos, k, v, hidden_in=None, tokens=tok)
+        srt = np.sort(lg, axis=1)
+        margins.append((srt[:, -1] - srt[:, -2]) / rms(lg))
+        tok = lg.argmax(axis=1).astype(np.int32)
+        ref_tokens.append(tok.copy())
+        pos = pos + 1
+    # one launch
+    f = F.fleet_create(sh.asdict(), m.w, sched, 0, 0)
+    kc, vc = m.kc.clone(), m.vc.clone()
+    tok_d = torch.tensor(tok0, device="cuda")
+    pos_d = torch.tensor(pos0, device="cuda")
+    out = torch.full((n_tokens, batch), -1, device="cuda", dtype=torch.int32)
+    hout = torch.zeros((batch, sh.hidden), device="cuda", dtype=torch.float32)
+    logits = torch.zeros((batch, sh.vocab), device="cuda", dtype=torch.float32)
+    F.fleet_decode_tokens(f, batch, tok_d, kc, vc, pos_d, n_tokens, out, hout, logits)
+    st = F.fleet_last_status(f)
+    F.fleet_destroy(f)
+    assert st["code"] == 0, st
+    got = out.cpu().numpy()
+    assert np.array_equal(pos_d.cpu().numpy(), pos0 + n_tokens)
+    assert np.array_equal(tok_d.cpu().numpy(), got[-1])
+    alive = np.ones(batch, bool)            # sequences that have not met a near-tie yet
+    for i in range(n_tokens):
+        # the step's logits agree to TOL * RMS at worst and to a few 1e-3 * RMS in practice (see
+        # the two-layer parity tests): a margin of TOL / 2 leaves no doubt about the winner
+        clear = margins[i] > TOL / 2
+        check = alive & clear
+        assert np.array_equal(got[i][check], ref_tokens[i][check]), (i, got[i], ref_tokens[i])
+        alive &= clear & (got[i] == ref_tokens[i])
+    print("  sequences compared to the end:", int(alive.sum()), "of", batch, flush=True)
+    assert alive.sum() >= (batch + 1) // 2
+    if alive.all():
+        assert_close(logits.cpu().numpy(), lg, "logits of the last step")
 
 
 def test_dependency_order_from_trace():
