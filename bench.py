@@ -27,21 +27,22 @@ HBM_PEAK_GBPS = 8000.0
 # same counters read for a plain copy of known size.  Key: (batch, kv, kv_min, sched, tile_m, flags)
 # at 36 layers and seed 2; any other workload reports null unless --traffic-bytes is given.
 MEASURED_TRAFFIC = {
-    (1, 1024, 0, 0, 0, 0): 15440332825,
-    (1, 1024, 0, 1, 0, 0): 15461265491,
-    (1, 1024, 0, 0, 0, 64): 16254256402,
-    (8, 2048, 1024, 0, 0, 0): 17313596060,
-    (8, 2048, 1024, 1, 0, 0): 17375794911,
-    (32, 2048, 1024, 0, 0, 0): 23402983460,
-    (32, 2048, 1024, 0, 16, 0): 26000035665,
-    (32, 2048, 1024, 1, 16, 0): 34632305872,
-    (32, 2048, 1024, 2, 16, 0): 38188532918,
-    (64, 4096, 0, 0, 0, 0): 56764363720,
-    (64, 4096, 0, 0, 16, 0): 60882509420,
-    (64, 4096, 0, 1, 16, 0): 86866980401,
-    (64, 4096, 0, 2, 16, 0): 100676571220,
-    (64, 4096, 0, 0, 16, 32): 58229367874,
-    (64, 4096, 0, 0, 16, 64): 56639297422,
+    (1, 1024, 0, 0, 0, 0): 15445712698,
+    (1, 1024, 0, 1, 0, 0): 15447655951,
+    (1, 1024, 0, 0, 0, 64): 16272874834,
+    (1, 1024, 0, 0, 0, 256): 16262773972,
+    (8, 2048, 1024, 0, 0, 0): 17080959405,
+    (8, 2048, 1024, 1, 0, 0): 17178598285,
+    (32, 2048, 1024, 0, 0, 0): 23369113135,
+    (32, 2048, 1024, 0, 16, 0): 26438532972,
+    (32, 2048, 1024, 1, 16, 0): 34826428209,
+    (32, 2048, 1024, 2, 16, 0): 38229714476,
+    (64, 4096, 0, 0, 0, 0): 57006717679,
+    (64, 4096, 0, 0, 16, 0): 61702129983,
+    (64, 4096, 0, 1, 16, 0): 87191952872,
+    (64, 4096, 0, 2, 16, 0): 100760256466,
+    (64, 4096, 0, 0, 16, 32): 58929626766,
+    (64, 4096, 0, 0, 16, 64): 56721391855,
 }
 
 
@@ -49,7 +50,7 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--kv", type=int, default=1024, help="valid KV slots per sequence before the step")
     ap.add_argument("--kv-min", type=int, default=0, help="if > 0, per-sequence lengths uniform in [kv-min, kv]")
