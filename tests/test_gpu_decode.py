@@ -142,6 +142,31 @@ def test_greedy_tokens_in_one_launch(batch, sched):
         assert_close(logits.cpu().numpy(), lg, "logits of the last step")
 
 
+def test_greedy_tokens_past_capacity_is_reported():
+    """A multi-step launch that would run past the KV capacity stops with FLEET_EINVAL in the
+    status (the kernel checks every position it is about to use) instead of touching memory
+    beyond the cache; bad arguments are refused on the host."""
+    sh = si.reduced_shape(max_batch=2, max_seq=32, n_layers=1, vocab=512)
+    m = Model(sh, seed=41, batch=2, positions=[3, 29], with_embed=True)
+    f = F.fleet_create(sh.asdict(), m.w, 0, 0, 0)
+    tok = torch.tensor([1, 2], device="cuda", dtype=torch.int32)
+    pos = torch.tensor([3, 29], device="cuda", dtype=torch.int32)
+    out = torch.full((8, 2), -1, device="cuda", dtype=torch.int32)
+    hout = torch.zeros((2, sh.hidden), device="cuda", dtype=torch.float32)
+    logits = torch.zeros((2, sh.vocab), device="cuda", dtype=torch.float32)
+    with pytest.raises(F.FleetError):
+        F.fleet_decode_tokens(f, 2, tok, m.kc, m.vc, pos, 0, out, hout, logits)          # no steps
+    with pytest.raises(F.FleetError):
+        F.fleet_decode_tokens(f, 3, tok, m.kc, m.vc, pos, 2, out, hout, logits)          # batch > max_batch
+    F.fleet_decode_tokens(f, 2, tok, m.kc.clone(), m.vc.clone(), pos, 8, out, hout, logits)   # 29 + 8 > 32
+    st = F.fleet_last_status(f)
+    F.fleet_destroy(f)
+    print("status:", st, flush=True)
+    assert st["code"] == -1
+    got = out.cpu().numpy()
+    assert (got[:3] >= 0).all()      # the steps that fit were made
+
+
 def test_dependency_order_from_trace():
     """Every task ran exactly once (every tile of a chiplet-task once) and no task started
     before all tasks signalling its wait event had ended: tickets from one device counter."""
