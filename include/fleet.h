@@ -167,6 +167,23 @@ int fleet_decode_layers(fleet_t *f, int32_t batch, int32_t layer_begin, int32_t 
 int fleet_destroy(fleet_t *f);
 
 /*
+ * fleet_decode_step_paged: fleet_decode_step over a paged KV cache.
+ *   k_pool, v_pool  device bf16 [n_layers][n_pages][n_kv][page_size][head_dim]: a page holds
+ *              page_size consecutive slots of one sequence, for every kv head of one layer
+ *   page_table device int32 [batch][table_stride]: entry i of a sequence is the page that
+ *              holds its slots i*page_size .. (the same page index in every layer)
+ *   page_size  a power of two >= 64; positions[b] < table_stride * page_size and < max_seq
+ * Everything else as in fleet_decode_step.  A page index outside [0, n_pages) or a position
+ * beyond the table ends the step with FLEET_EINVAL in the status; nothing is read or
+ * written through such an entry.
+ */
+int fleet_decode_step_paged(fleet_t *f, int32_t batch, const void *hidden_in, const int32_t *tokens,
+                            void *k_pool, void *v_pool, const int32_t *page_table,
+                            int32_t page_size, int32_t n_pages, int32_t table_stride,
+                            const int32_t *positions, float *hidden_out, float *logits,
+                            void *stream);
+
+/*
  * fleet_decode_tokens: n_tokens greedy decode steps in ONE launch of the persistent kernel
  * (paper section 4.1: the kernel stays resident over the generated tokens; no return to the
  * host between steps).  Each step gathers embed[tokens[b]], runs the decoder stack and the LM

@@ -20,7 +20,8 @@ FLAG_TRACE, FLAG_SINGLE_LEVEL, FLAG_SEPARATE_NORM, FLAG_CHAINED, FLAG_TIMING = 1
 FLAG_NO_SPLITK, FLAG_NO_STREAM, FLAG_NO_RESIDENT, FLAG_UNFUSED_SILU = 32, 64, 128, 256
 
 EXPORTS = (
-    "fleet_create", "fleet_decode_step", "fleet_decode_layers", "fleet_decode_tokens", "fleet_destroy",
+    "fleet_create", "fleet_decode_step", "fleet_decode_step_paged", "fleet_decode_layers",
+    "fleet_decode_tokens", "fleet_destroy",
     "fleet_gemm",
     "fleet_graph_build", "fleet_graph_dump", "fleet_trace_read", "fleet_last_status",
     "fleet_device_probe", "fleet_copy", "fleet_weight_bytes", "fleet_weight_bytes_per_xcd",
@@ -148,6 +149,17 @@ def fleet_decode_layers(f: Fleet, batch: int, layer_begin: int, layer_end: int, 
                                             _ptr(logits), C.c_void_p(stream))
     if rc != 0:
         raise FleetError(rc, "fleet_decode_layers")
+
+
+def fleet_decode_step_paged(f: Fleet, batch: int, hidden_in, tokens, k_pool, v_pool, page_table,
+                            page_size: int, n_pages: int, table_stride: int, positions, hidden_out,
+                            logits=None, stream=0) -> None:
+    rc = load_library().fleet_decode_step_paged(
+        f.handle, C.c_int32(batch), _ptr(hidden_in), _ptr(tokens), _ptr(k_pool), _ptr(v_pool),
+        _ptr(page_table), C.c_int32(page_size), C.c_int32(n_pages), C.c_int32(table_stride),
+        _ptr(positions), _ptr(hidden_out), _ptr(logits), C.c_void_p(stream))
+    if rc != 0:
+        raise FleetError(rc, "fleet_decode_step_paged")
 
 
 def fleet_decode_tokens(f: Fleet, batch: int, tokens, k_cache, v_cache, positions, n_tokens: int,

@@ -71,7 +71,18 @@ int pack_matrix(void** dst, const void* src, int rows, int K, bool by_unit) {
 }
 
 // the persistent kernel compiled for one GEMM flavour (see dev::N_VARIANTS)
-const void* kernel_variant(int v) {
+const void* kernel_variant(int v, bool paged = false) {
+  if (paged) {
+    switch (v) {
+      case 0: return (const void*)fleet_persistent_kernel<0, true>;
+      case 1: return (const void*)fleet_persistent_kernel<1, true>;
+      case 2: return (const void*)fleet_persistent_kernel<2, true>;
+      case 3: return (const void*)fleet_persistent_kernel<3, true>;
+      case 4: return (const void*)fleet_persistent_kernel<4, true>;
+      case 5: return (const void*)fleet_persistent_kernel<5, true>;
+      default: return (const void*)fleet_persistent_kernel<6, true>;
+    }
+  }
   switch (v) {
     case 0: return (const void*)fleet_persistent_kernel<0>;
     case 1: return (const void*)fleet_persistent_kernel<1>;
@@ -117,7 +128,7 @@ int launch_persistent(DevGraph* dg, dev::Params& P, int n_cu, hipStream_t st) {
     P.first_wait_event = dg->memo_first; P.last_wait_event = dg->memo_last;
   }
   void* args[] = {(void*)&P};
-  HIP_TRY(hipLaunchKernel(kernel_variant(v), dim3(n_cu), dim3(dev::WG), args, LDS_BYTES, st));
+  HIP_TRY(hipLaunchKernel(kernel_variant(v, P.page_size > 0), dim3(n_cu), dim3(dev::WG), args, LDS_BYTES, st));
   return FLEET_OK;
 }
 
@@ -128,8 +139,10 @@ int prepare_kernel() {
   HIP_TRY(hipGetDevice(&dev_id));
   HIP_TRY(hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev_id));
   if ((size_t)lds < LDS_BYTES + 4096) return FLEET_EDEVICE;
-  for (int v = 0; v < dev::N_VARIANTS; ++v)
+  for (int v = 0; v < dev::N_VARIANTS; ++v) {
     HIP_TRY(hipFuncSetAttribute(kernel_variant(v), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES));
+    HIP_TRY(hipFuncSetAttribute(kernel_variant(v, true), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES));
+  }
   HIP_TRY(hipFuncSetAttribute((const void*)fleet_probe_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES));
   int per_cu = 0;
   HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fleet_persistent_kernel<6>, dev::WG, LDS_BYTES));
@@ -304,10 +317,16 @@ int get_graph(fleet* f, int batch, DevGraph** out, bool loop = false) {
   cache[batch] = std::move(dg);
   return FLEET_OK;
 }
+struct KvPaging {   // paged KV cache: k_cache / v_cache are page pools
+  const int32_t* table = nullptr;   // device [batch][stride] page indices
+  int page_size = 0, n_pages = 0, stride = 0;
+};
+
 // n_tokens > 0: the whole step n_tokens times in one launch (graph with the next-token stage)
 int run_layers(fleet* f, int batch, int layer_begin, int layer_end, bool with_ingest, bool with_final,
                const void* hidden_in, const int32_t* tokens, void* k_cache, void* v_cache, const int32_t* positions,
-               float* hidden_out, float* logits, hipStream_t st, int n_tokens = 0, int32_t* tokens_out = nullptr) {
+               float* hidden_out, float* logits, hipStream_t st, int n_tokens = 0, int32_t* tokens_out = nullptr,
+               const KvPaging* paging = nullptr) {
   DevGraph* dg = nullptr;
   int rc = get_graph(f, batch, &dg, n_tokens > 0);
   if (rc) return rc;
@@ -321,6 +340,10 @@ int run_layers(fleet* f, int batch, int layer_begin, int layer_end, bool with_in
   P.buf[BUF_KC] = k_cache; P.buf[BUF_VC] = v_cache; P.buf[BUF_POS] = (void*)positions;
   P.buf[BUF_HIDDEN_OUT] = hidden_out; P.buf[BUF_LOGITS] = logits; P.buf[BUF_TOKENS_OUT] = tokens_out;
   P.n_iter = n_tokens > 0 ? n_tokens : 1;
+  if (paging) {
+    P.buf[BUF_PT] = (void*)paging->table;
+    P.page_size = paging->page_size; P.n_pages = paging->n_pages; P.pt_stride = paging->stride;
+  }
   P.status = f->status; P.trace_cap = TRACE_CAP;
   // (no trace of a multi-step launch: the record area holds one step)
   P.trace = (n_tokens == 0 && (f->shape.flags & (FLEET_FLAG_TRACE | FLEET_FLAG_TIMING))) ? f->trace : nullptr;
@@ -481,6 +504,23 @@ int fleet_decode_layers(fleet_t* f, int32_t batch, int32_t layer_begin, int32_t 
   if (rc) return rc;
   if (!fin) HIP_TRY(hipMemcpyAsync(x_out, f->x, bytes, hipMemcpyDeviceToDevice, st));
   return FLEET_OK;
+}
+
+int fleet_decode_step_paged(fleet_t* f, int32_t batch, const void* hidden_in, const int32_t* tokens, void* k_pool,
+                            void* v_pool, const int32_t* page_table, int32_t page_size, int32_t n_pages,
+                            int32_t table_stride, const int32_t* positions, float* hidden_out, float* logits,
+                            void* stream) {
+  if (!f || batch < 1 || batch > f->shape.max_batch || !k_pool || !v_pool || !positions || !hidden_out || !page_table)
+    return FLEET_EINVAL;
+  if (!hidden_in && !(tokens && f->embed)) return FLEET_EINVAL;
+  if (!logits && f->shape.vocab > 0) return FLEET_EINVAL;   // the LM head is part of the step
+  if (page_size < 64 || (page_size & (page_size - 1)) || n_pages < 1 || table_stride < 1) return FLEET_EINVAL;
+  // the kernel addresses a page with 32-bit page arithmetic inside one layer's pool
+  if ((int64_t)n_pages * f->shape.n_kv_heads * page_size > (int64_t)1 << 40) return FLEET_EINVAL;
+  KvPaging pg;
+  pg.table = page_table; pg.page_size = page_size; pg.n_pages = n_pages; pg.stride = table_stride;
+  return run_layers(f, batch, 0, f->shape.n_layers, true, true, hidden_in, tokens, k_pool, v_pool, positions, hidden_out,
+                    logits, (hipStream_t)stream, 0, nullptr, &pg);
 }
 
 int fleet_decode_tokens(fleet_t* f, int32_t batch, int32_t* tokens, void* k_cache, void* v_cache, int32_t* positions,

@@ -50,7 +50,7 @@ constexpr int ATTN_TWO_LEVEL_MIN_PER_XCD = 8;
 // activation / caller buffers, resolved to pointers per step
 enum Buf {
   BUF_NONE = 0, BUF_X, BUF_N, BUF_QKV, BUF_ATT, BUF_H, BUF_PART, BUF_HIDDEN_IN, BUF_TOKENS,
-  BUF_KC, BUF_VC, BUF_POS, BUF_HIDDEN_OUT, BUF_LOGITS, BUF_GEMM_X, BUF_GEMM_Y, BUF_GPART, BUF_GU32, BUF_TOKENS_OUT, N_BUF
+  BUF_KC, BUF_VC, BUF_POS, BUF_HIDDEN_OUT, BUF_LOGITS, BUF_GEMM_X, BUF_GEMM_Y, BUF_GPART, BUF_GU32, BUF_TOKENS_OUT, BUF_PT, N_BUF
 };
 
 // which caller weight an op reads (resolved with the op's layer)
