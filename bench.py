@@ -27,22 +27,21 @@ HBM_PEAK_GBPS = 8000.0
 # same counters read for a plain copy of known size.  Key: (batch, kv, kv_min, sched, tile_m, flags)
 # at 36 layers and seed 2; any other workload reports null unless --traffic-bytes is given.
 MEASURED_TRAFFIC = {
-    (1, 1024, 0, 0, 0, 0): 15445712698,
-    (1, 1024, 0, 1, 0, 0): 15447655951,
-    (1, 1024, 0, 0, 0, 64): 16272874834,
-    (1, 1024, 0, 0, 0, 256): 16262773972,
-    (8, 2048, 1024, 0, 0, 0): 17080959405,
-    (8, 2048, 1024, 1, 0, 0): 17178598285,
-    (32, 2048, 1024, 0, 0, 0): 23369113135,
-    (32, 2048, 1024, 0, 16, 0): 26438532972,
-    (32, 2048, 1024, 1, 16, 0): 34826428209,
-    (32, 2048, 1024, 2, 16, 0): 38229714476,
-    (64, 4096, 0, 0, 0, 0): 57006717679,
-    (64, 4096, 0, 0, 16, 0): 61702129983,
-    (64, 4096, 0, 1, 16, 0): 87191952872,
-    (64, 4096, 0, 2, 16, 0): 100760256466,
-    (64, 4096, 0, 0, 16, 32): 58929626766,
-    (64, 4096, 0, 0, 16, 64): 56721391855,
+    (1, 1024, 0, 0, 0, 0): 15449602098,
+    (1, 1024, 0, 1, 0, 0): 15447247668,
+    (1, 1024, 0, 0, 0, 64): 16277970904,
+    (1, 1024, 0, 0, 0, 256): 16268661230,
+    (8, 2048, 1024, 0, 0, 0): 17079966442,
+    (8, 2048, 1024, 1, 0, 0): 17177812861,
+    (32, 2048, 1024, 0, 0, 0): 23350723031,
+    (32, 2048, 1024, 0, 16, 0): 23734428599,
+    (32, 2048, 1024, 1, 16, 0): 33005436105,
+    (32, 2048, 1024, 2, 16, 0): 38636745347,
+    (64, 4096, 0, 0, 0, 0): 56983320904,
+    (64, 4096, 0, 0, 16, 0): 56724305242,
+    (64, 4096, 0, 1, 16, 0): 85209153506,
+    (64, 4096, 0, 2, 16, 0): 101168675160,
+    (64, 4096, 0, 0, 16, 32): 55947853907,
 }
 
 
