@@ -385,3 +385,15 @@ def test_paper_task_counts_and_partition_pointers():
         if c["batch"] > 8:
             h = F.parse_graph(F.fleet_graph_build(sh64.asdict(), c["batch"], 8, 256, 0, 16))["header"]
             assert h["m_tiles"] == c["m_tiles"]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: any other --gpus value ends with a message and exit code 2,
+    before anything touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode == 2
+    assert "one GPU" in (res.stdout + res.stderr)
