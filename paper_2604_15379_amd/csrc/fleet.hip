@@ -279,7 +279,9 @@ int upload_graph(DevGraph* dg, const fleet* f, const void* const* gemm_copies, i
   // G[e], L[x][e], then one arrival counter per (sequence, kv head) for the split-KV merge
   // and one relay word per worker on its own cache line
   // (MFMA graphs: then the arrival counters of split-K GEMM tiles)
-  dg->gcnt_base = dev::C_EVENTS + g.n_events() * (1 + n_xcd) + dev::N_PAIR + n_xcd * dev::RELAY_SLOTS * dev::RELAY_STRIDE;
+  // (then one copy of the device counters per XCD, rows on their own cache lines)
+  dg->gcnt_base = dev::C_EVENTS + g.n_events() * (1 + n_xcd) + dev::N_PAIR + n_xcd * dev::RELAY_SLOTS * dev::RELAY_STRIDE +
+                  dev::COPY_GROUPS * n_xcd * ((g.n_events() + 31) & ~31);
   dg->ctr_words = dg->gcnt_base + (g.header[H_PATH] == P_MFMA ? dev::GEMM_CNT_WORDS : 0);
   if ((rc = upload(&dg->ctr, nullptr, (size_t)dg->ctr_words * 4))) return rc;
   return FLEET_OK;
@@ -294,8 +296,10 @@ int launch(dev::Params& P, DevGraph* dg, int n_cu, int preset_event, hipStream_t
     preset_word = dev::C_EVENTS + preset_event;
     preset_val = 0x40000000u;   // satisfied whatever the threshold
   }
+  const int nE = dg->g.n_events(), nx = dg->g.header[H_N_XCD], cstride = (nE + 31) & ~31;
+  const int cbase = dev::C_EVENTS + nE * (1 + nx) + dev::N_PAIR + nx * dev::RELAY_SLOTS * dev::RELAY_STRIDE;
   hipLaunchKernelGGL(fleet_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, st, dg->ctr, words, preset_word,
-                     preset_val, P.status);
+                     preset_val, P.status, cbase, cstride, dev::COPY_GROUPS * nx, preset_event);
   return launch_persistent(dg, P, n_cu, st);
 }
 
@@ -643,7 +647,7 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const
   if (he == hipSuccess) he = hipEventCreate(&e1);
   if (he == hipSuccess) {
     const int words = dg.ctr_words;
-    hipLaunchKernelGGL(fleet_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, st, dg.ctr, words, -1, 0u, status);
+    hipLaunchKernelGGL(fleet_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, st, dg.ctr, words, -1, 0u, status, 0, 1, 0, -1);
     (void)hipEventRecord(e0, st);
     int lrc = launch_persistent(&dg, P, info.n_cu, st);
     (void)hipEventRecord(e1, st);
