@@ -27,21 +27,21 @@ HBM_PEAK_GBPS = 8000.0
 # same counters read for a plain copy of known size.  Key: (batch, kv, kv_min, sched, tile_m, flags)
 # at 36 layers and seed 2; any other workload reports null unless --traffic-bytes is given.
 MEASURED_TRAFFIC = {
-    (1, 1024, 0, 0, 0, 0): 15449602098,
-    (1, 1024, 0, 1, 0, 0): 15447247668,
-    (1, 1024, 0, 0, 0, 64): 16277970904,
-    (1, 1024, 0, 0, 0, 256): 16268661230,
-    (8, 2048, 1024, 0, 0, 0): 17079966442,
-    (8, 2048, 1024, 1, 0, 0): 17177812861,
-    (32, 2048, 1024, 0, 0, 0): 23350723031,
-    (32, 2048, 1024, 0, 16, 0): 23734428599,
-    (32, 2048, 1024, 1, 16, 0): 33005436105,
-    (32, 2048, 1024, 2, 16, 0): 38636745347,
-    (64, 4096, 0, 0, 0, 0): 56983320904,
-    (64, 4096, 0, 0, 16, 0): 56724305242,
-    (64, 4096, 0, 1, 16, 0): 85209153506,
-    (64, 4096, 0, 2, 16, 0): 101168675160,
-    (64, 4096, 0, 0, 16, 32): 55947853907,
+    (1, 1024, 0, 0, 0, 0): 15422809388,
+    (1, 1024, 0, 1, 0, 0): 15432798844,
+    (1, 1024, 0, 0, 0, 64): 16230592811,
+    (1, 1024, 0, 0, 0, 256): 16231046586,
+    (8, 2048, 1024, 0, 0, 0): 17022194112,
+    (8, 2048, 1024, 1, 0, 0): 17154804315,
+    (32, 2048, 1024, 0, 0, 0): 23303497089,
+    (32, 2048, 1024, 0, 16, 0): 23717906243,
+    (32, 2048, 1024, 1, 16, 0): 33044265636,
+    (32, 2048, 1024, 2, 16, 0): 38630257332,
+    (64, 4096, 0, 0, 0, 0): 56902771043,
+    (64, 4096, 0, 0, 16, 0): 56685062959,
+    (64, 4096, 0, 1, 16, 0): 85282242473,
+    (64, 4096, 0, 2, 16, 0): 101124945875,
+    (64, 4096, 0, 0, 16, 32): 55919631610,
 }
 
 
