@@ -81,6 +81,26 @@ def test_schedules_agree_with_oracle(batch, sched, tile_m, flags):
     check_new_kv(m, got[2], got[3], k, v)
 
 
+def test_one_fleet_many_batch_sizes():
+    """One fleet_t serves steps of different batch sizes in any order (a graph per batch size,
+    built on first use and cached; shared scratch activations and counters): every step equals
+    the oracle, including repeats of a size seen before."""
+    sh = si.reduced_shape(max_batch=40, max_seq=96, n_layers=2, vocab=1024)
+    base = Model(sh, seed=70, batch=40, positions=np.random.default_rng(70).integers(0, 96, 40).astype(np.int32))
+    f = F.fleet_create(sh.asdict(), base.w, 0, 0, 0)
+    try:
+        for batch in (1, 5, 40, 2, 5, 17, 1):
+            print(f"  step with batch {batch}", flush=True)
+            pos = np.random.default_rng(100 + batch).integers(0, 96, batch).astype(np.int32)
+            m = Model(sh, seed=70, batch=batch, positions=pos)   # same seed: same weights as the fleet's
+            (ho, lg), k, v = m.run_oracle()
+            got = m.run_gpu(fleet=f)
+            assert_close(got[0], ho, f"hidden_out batch {batch}")
+            assert_close(got[1], lg, f"logits batch {batch}")
+    finally:
+        F.fleet_destroy(f)
+
+
 def test_embedding_gather_input():
     sh = si.reduced_shape(max_batch=4, max_seq=64, n_layers=1, vocab=512)
     m = Model(sh, seed=5, batch=4, positions=[3, 63, 0, 17], with_embed=True)
