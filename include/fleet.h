@@ -66,12 +66,12 @@ enum fleet_flags {
   FLEET_FLAG_NO_RESIDENT = 128,/* MFMA GEMMs: never hold a worker's whole weight share in
                                   registers across the dependency wait (small GEMMs then
                                   use split-K tiles)                                    */
-  FLEET_FLAG_LEADER_RELAY = 512,/* only the leader (rank 0) of an XCD polls the device counter and
-                                  relays it to a word per follower, instead of every worker
-                                  polling one of the per-XCD copies of the counter        */
-  FLEET_FLAG_UNFUSED_SILU = 256/* gate|up GEMM stores its fp32 sums; SiLU(gate) x up runs as
+  FLEET_FLAG_UNFUSED_SILU = 256,/* gate|up GEMM stores its fp32 sums; SiLU(gate) x up runs as
                                   a stage of CU-tasks of its own (section 3.2, operator
                                   fusion ablation)                                      */
+  FLEET_FLAG_LEADER_RELAY = 512 /* only the leader (rank 0) of an XCD polls the device counter
+                                  and relays it to a word per follower, instead of every
+                                  worker polling one of the per-XCD copies of the counter */
 };
 
 typedef struct {
