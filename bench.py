@@ -27,21 +27,21 @@ HBM_PEAK_GBPS = 8000.0
 # same counters read for a plain copy of known size.  Key: (batch, kv, kv_min, sched, tile_m, flags)
 # at 36 layers and seed 2; any other workload reports null unless --traffic-bytes is given.
 MEASURED_TRAFFIC = {
-    (1, 1024, 0, 0, 0, 0): 15422809388,
-    (1, 1024, 0, 1, 0, 0): 15432798844,
-    (1, 1024, 0, 0, 0, 64): 16230592811,
-    (1, 1024, 0, 0, 0, 256): 16231046586,
-    (8, 2048, 1024, 0, 0, 0): 17022194112,
-    (8, 2048, 1024, 1, 0, 0): 17154804315,
-    (32, 2048, 1024, 0, 0, 0): 23303497089,
-    (32, 2048, 1024, 0, 16, 0): 23717906243,
-    (32, 2048, 1024, 1, 16, 0): 33044265636,
-    (32, 2048, 1024, 2, 16, 0): 38630257332,
-    (64, 4096, 0, 0, 0, 0): 56902771043,
-    (64, 4096, 0, 0, 16, 0): 56685062959,
-    (64, 4096, 0, 1, 16, 0): 85282242473,
-    (64, 4096, 0, 2, 16, 0): 101124945875,
-    (64, 4096, 0, 0, 16, 32): 55919631610,
+    (1, 1024, 0, 0, 0, 0): 15418874715,
+    (1, 1024, 0, 1, 0, 0): 15426810009,
+    (1, 1024, 0, 0, 0, 64): 16199707146,
+    (1, 1024, 0, 0, 0, 256): 16224248351,
+    (8, 2048, 1024, 0, 0, 0): 17006675863,
+    (8, 2048, 1024, 1, 0, 0): 17143443560,
+    (32, 2048, 1024, 0, 0, 0): 23225353483,
+    (32, 2048, 1024, 0, 16, 0): 23632941537,
+    (32, 2048, 1024, 1, 16, 0): 33014088005,
+    (32, 2048, 1024, 2, 16, 0): 38529754381,
+    (64, 4096, 0, 0, 0, 0): 56205216775,
+    (64, 4096, 0, 0, 16, 0): 56600692620,
+    (64, 4096, 0, 1, 16, 0): 85322344633,
+    (64, 4096, 0, 2, 16, 0): 101034121023,
+    (64, 4096, 0, 0, 16, 32): 55833685966,
 }
 
 
