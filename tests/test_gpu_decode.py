@@ -81,6 +81,34 @@ def test_schedules_agree_with_oracle(batch, sched, tile_m, flags):
     check_new_kv(m, got[2], got[3], k, v)
 
 
+@pytest.mark.parametrize("batch", [1, 3])          # FMA-path kernel, MFMA-path kernel
+@pytest.mark.parametrize("ramp", ["up", "down", "wave"])
+def test_attention_scores_of_wide_range(batch, ramp):
+    """Keys whose magnitude changes along the cache by a factor of 160 give scores that span
+    some +-70 binades.  The kernel's running softmax moves its reference score only when a
+    score exceeds it by more than 10 binades: growing keys ("up") force such moves again and
+    again in every stream, shrinking ones ("down") put the largest score first, and "wave"
+    alternates.  Second run: every cached value vector of a head is the same vector, so the
+    attention output must be that vector whatever the weights are -- the sum of the weights
+    and the weighted sum have to be rescaled alike."""
+    print(f"wide-range scores batch={batch} ramp={ramp}", flush=True)
+    sh = si.reduced_shape(max_batch=batch, max_seq=600, n_layers=1, vocab=0)
+    pos = [599, 300, 77][:batch]
+    slot = torch.arange(sh.max_seq, device="cuda", dtype=torch.float32)
+    gain = {"up": 0.1 + 15.9 * slot / (sh.max_seq - 1),
+            "down": 16.0 - 15.9 * slot / (sh.max_seq - 1),
+            "wave": 8.05 + 7.95 * torch.sin(slot * 0.05)}[ramp]
+    for same_v in (False, True):
+        m = Model(sh, seed=21, batch=batch, positions=pos)
+        m.kc = (m.kc.float() * gain[None, None, None, :, None]).to(torch.bfloat16)
+        if same_v:
+            m.vc = m.vc[:, :, :, :1, :].expand_as(m.vc).contiguous()
+        (ho, _), k, v = m.run_oracle()
+        got = m.run_gpu()
+        assert_close(got[0], ho, f"hidden_out same_v={same_v}")
+        check_new_kv(m, got[2], got[3], k, v)
+
+
 def test_one_fleet_many_batch_sizes():
     """One fleet_t serves steps of different batch sizes in any order (a graph per batch size,
     built on first use and cached; shared scratch activations and counters): every step equals
