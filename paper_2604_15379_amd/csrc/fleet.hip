@@ -199,6 +199,7 @@ struct fleet {
   // scratch activations (device)
   float* x = nullptr; void* n = nullptr; float* qkv = nullptr; void* att = nullptr; void* h = nullptr;
   float* part = nullptr; float* gpart = nullptr; float* gu32 = nullptr; float2* rope = nullptr;
+  size_t gpart_bytes = 0;   // bytes of one region of gpart
   int32_t* status = nullptr; int32_t* trace = nullptr;
   std::map<int, std::unique_ptr<DevGraph>> graphs;        // by batch size
   std::map<int, std::unique_ptr<DevGraph>> graphs_loop;   // with the next-token stage (multi-step launches)
@@ -344,6 +345,7 @@ int run_layers(fleet* f, int batch, int layer_begin, int layer_end, bool with_in
   P.buf[BUF_KC] = k_cache; P.buf[BUF_VC] = v_cache; P.buf[BUF_POS] = (void*)positions;
   P.buf[BUF_HIDDEN_OUT] = hidden_out; P.buf[BUF_LOGITS] = logits; P.buf[BUF_TOKENS_OUT] = tokens_out;
   P.n_iter = n_tokens > 0 ? n_tokens : 1;
+  P.gpart_xcd_bytes = f->shape.sched_mode == FLEET_SCHED_UNAWARE ? 0 : (int32_t)f->gpart_bytes;
   if (paging) {
     P.buf[BUF_PT] = (void*)paging->table;
     P.page_size = paging->page_size; P.n_pages = paging->n_pages; P.pt_stride = paging->stride;
@@ -444,7 +446,9 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
   if (shape->max_batch > fma_max_batch()) {
     size_t nmax = std::max({NQKV, H, 2 * F});
     if (shape->vocab > 0 && (size_t)shape->vocab / 16 * 4 <= (size_t)GEMM_TILE_COUNTERS) nmax = std::max(nmax, (size_t)shape->vocab);
-    if ((rc = upload(&f->gpart, nullptr, 8 * 64 * nmax * 4))) return rc;
+    // (a region per XCD under the XCD-aware schedules)
+    f->gpart_bytes = 8 * 64 * nmax * 4;
+    if ((rc = upload(&f->gpart, nullptr, f->gpart_bytes * (shape->sched_mode == FLEET_SCHED_UNAWARE ? 1 : dev::MAX_XCD)))) return rc;
   }
   if (shape->flags & FLEET_FLAG_UNFUSED_SILU)   // fp32 [gate | up] sums of the unfused gate|up GEMM
     if ((rc = upload(&f->gu32, nullptr, mb * 2 * F * 4))) return rc;
@@ -632,11 +636,13 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const
   int32_t* status = nullptr;
   if ((rc = upload(&status, nullptr, dev::ST_WORDS * 4))) { free_packed(); return rc; }
   float* gpart = nullptr;   // partial sums of split-K tiles
-  if ((rc = upload(&gpart, nullptr, (size_t)8 * 64 * N * 4))) { (void)hipFree(status); free_packed(); return rc; }
+  const size_t gpart_bytes = (size_t)8 * 64 * N * 4;   // one region; one per XCD under the XCD-aware schedules
+  if ((rc = upload(&gpart, nullptr, gpart_bytes * (sched_mode == FLEET_SCHED_UNAWARE ? 1 : dev::MAX_XCD)))) { (void)hipFree(status); free_packed(); return rc; }
   dev::Params P;
   memset(&P, 0, sizeof(P));
   fill_graph_params(P, &dg);
   P.buf[BUF_GEMM_X] = mfma ? xp : (void*)x; P.buf[BUF_GEMM_Y] = y; P.buf[BUF_GPART] = gpart;
+  P.gpart_xcd_bytes = sched_mode == FLEET_SCHED_UNAWARE ? 0 : (int32_t)gpart_bytes;
   P.n_iter = 1;
   P.status = status; P.timeout_ticks = timeout_ticks_from_env(); P.n_xcd = info.n_xcd; P.flags = flags;
   P.batch = B; P.hidden = K;
