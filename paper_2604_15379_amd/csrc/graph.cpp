@@ -53,8 +53,7 @@ struct Builder {
   // the cooperative schedule (round-robin inside the XCD), to any worker in the
   // chiplet-unaware one.  args(i) fills A0..A3.  Returns the signalled event.
   // Few tasks per XCD (at most min_per_xcd on average): each signals the device counter itself
-  // (one atomic less on the path).  More: two-level, one release and one device-level signal
-  // per XCD.
+  // (one atomic less on the path).  More: two-level, one device-level signal per XCD.
   template <class KeyF, class ArgF>
   int cu_stage(int op, int n_items, int wait_ev, KeyF key, ArgF args, int min_per_xcd = 1) {
     int ev;
@@ -339,8 +338,8 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
     ev = b.cu_stage(op_att, batch * nkv * S, ev,
                     [S](int i) { return i / S; },
                     [S, nkv](int i, int* a) { int p = i / S; a[0] = p / nkv; a[1] = p % nkv; a[2] = i % S; a[3] = S; },
-                    // splits that do not merge publish nothing and skip the release when they
-                    // signal directly: two-level pays only with many tasks per XCD
+                    // every direct signal is 17 atomics (the device counter and its copies):
+                    // measured, two-level pays for attention only with many tasks per XCD
                     ATTN_TWO_LEVEL_MIN_PER_XCD);
 
     // FMA path, cooperative: the O projection's idle workers warm the L2 with the first weight

@@ -44,8 +44,9 @@ enum Dist { D_CHIPLET = 0, D_XCD_RR = 1, D_DEV_RR = 2 };
 // grouped per XCD (cooperative schedule); EV_DIRECT: by CU-tasks running anywhere
 enum EventKind { EV_DIRECT = 0, EV_TWO_LEVEL = 1, EV_TWO_LEVEL_CU = 2 };
 // a stage of CU-tasks signals two-level when it has more than one task per XCD on average
-// (attention stages: more than this many)
-constexpr int ATTN_TWO_LEVEL_MIN_PER_XCD = 8;
+// (attention stages: more than this many -- measured: with up to 32 tasks per XCD the direct
+// signals are 1 % of a step faster at batch 2 and 8, the same at batch 32)
+constexpr int ATTN_TWO_LEVEL_MIN_PER_XCD = 32;
 
 // activation / caller buffers, resolved to pointers per step
 enum Buf {

@@ -235,7 +235,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
                        xm(H) | plan(NQKV // ur, H, 1))
         ev = gemm_stage(o_qkv, ev)
         att_items = [(p, [p // nkv, p % nkv, s, S]) for p in range(batch * nkv) for s in range(S)]
-        ev = cu_stage(op(ATTN, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["QKV"], BUF["ATT"], S, WK["NONE"]), att_items, ev, 8)
+        ev = cu_stage(op(ATTN, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["QKV"], BUF["ATT"], S, WK["NONE"]), att_items, ev, 32)
         # FMA path, cooperative: the O projection carries the gate/up matrix as second pointer
         # (low byte of aux2) and its gate rows (aux): idle workers warm the L2 with it
         # -- only where attention keeps at most a quarter of every XCD's workers busy
