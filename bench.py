@@ -27,21 +27,21 @@ HBM_PEAK_GBPS = 8000.0
 # same counters read for a plain copy of known size.  Key: (batch, kv, kv_min, sched, tile_m, flags)
 # at 36 layers and seed 2; any other workload reports null unless --traffic-bytes is given.
 MEASURED_TRAFFIC = {
-    (1, 1024, 0, 0, 0, 0): 15418874715,
-    (1, 1024, 0, 1, 0, 0): 15426810009,
-    (1, 1024, 0, 0, 0, 64): 16199707146,
-    (1, 1024, 0, 0, 0, 256): 16224248351,
-    (8, 2048, 1024, 0, 0, 0): 17006675863,
-    (8, 2048, 1024, 1, 0, 0): 17143443560,
-    (32, 2048, 1024, 0, 0, 0): 23225353483,
-    (32, 2048, 1024, 0, 16, 0): 23632941537,
-    (32, 2048, 1024, 1, 16, 0): 33014088005,
-    (32, 2048, 1024, 2, 16, 0): 38529754381,
-    (64, 4096, 0, 0, 0, 0): 56205216775,
-    (64, 4096, 0, 0, 16, 0): 56600692620,
-    (64, 4096, 0, 1, 16, 0): 85322344633,
-    (64, 4096, 0, 2, 16, 0): 101034121023,
-    (64, 4096, 0, 0, 16, 32): 55833685966,
+    (1, 1024, 0, 0, 0, 0): 15451158829,
+    (1, 1024, 0, 1, 0, 0): 15439029837,
+    (1, 1024, 0, 0, 0, 64): 16207029003,
+    (1, 1024, 0, 0, 0, 256): 16278494002,
+    (8, 2048, 1024, 0, 0, 0): 17068094469,
+    (8, 2048, 1024, 1, 0, 0): 17152472441,
+    (32, 2048, 1024, 0, 0, 0): 23348117375,
+    (32, 2048, 1024, 0, 16, 0): 23808980598,
+    (32, 2048, 1024, 1, 16, 0): 33118030447,
+    (32, 2048, 1024, 2, 16, 0): 38699212205,
+    (64, 4096, 0, 0, 0, 0): 56627795873,
+    (64, 4096, 0, 0, 16, 0): 56956602653,
+    (64, 4096, 0, 1, 16, 0): 85357886606,
+    (64, 4096, 0, 2, 16, 0): 101380100752,
+    (64, 4096, 0, 0, 16, 32): 56175329948,
 }
 
 
