@@ -127,6 +127,10 @@ typedef struct {
  * allocate descriptors, counters and scratch activations, build the RoPE table, and
  * (max_batch on the MFMA path) repack the GEMM weights into a private copy.
  * Paper section 4.3 (task registration at model load).  *out is set on success.
+ * Device memory the library owns besides that copy: the activations of one step
+ * (a few MB), and, on the MFMA path, the partial sums of split-K GEMM tiles: 8 k-slices x
+ * 64 rows x the widest GEMM output, fp32, once per XCD under the XCD-aware schedules
+ * (8 x 50 MB for the Qwen3-8B shape).
  * Requirements: head_dim == 128, hidden/ffn/(nq*head_dim) multiples of 16,
  * n_q_heads a multiple of n_kv_heads with ratio <= 4, vocab a multiple of 16,
  * hidden and ffn multiples of 32.
@@ -150,6 +154,9 @@ int fleet_create(const fleet_shape_t *shape, const fleet_weights_t *weights, fle
  * graph (host work + one device allocation); later calls only launch.
  * A dependency wait that times out aborts the step on the device; the next
  * fleet_last_status() reports FLEET_ETIMEOUT.
+ * The result is a function of the inputs alone: every reduction has a fixed order, so
+ * repeating the step on the same inputs gives the same bits (for a given batch size,
+ * schedule and tile height).
  */
 int fleet_decode_step(fleet_t *f, int32_t batch, const void *hidden_in, const int32_t *tokens,
                       void *k_cache, void *v_cache, const int32_t *positions,
