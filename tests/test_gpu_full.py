@@ -152,15 +152,17 @@ def test_batch64_kv4096_cooperative_and_unaware(weights):
     _check(c, F.SCHED_COOPERATIVE, 0, free_running=False)
 
 
-@pytest.mark.parametrize("batch,kv_lo,kv_hi,reps", [(8, 1024, 2048, 200), (32, 1024, 2048, 120), (2, 1024, 2048, 200)])
-def test_repeated_steps_give_identical_bits(weights, batch, kv_lo, kv_hi, reps):
+@pytest.mark.parametrize("batch,kv_lo,kv_hi,reps,sched,tile_m", [
+    (8, 1024, 2048, 200, 0, 0), (32, 1024, 2048, 120, 0, 0), (2, 1024, 2048, 200, 0, 0),
+    (8, 1024, 2048, 100, F.SCHED_UNAWARE, 0), (32, 1024, 2048, 80, F.SCHED_MSPLIT, 16)])
+def test_repeated_steps_give_identical_bits(weights, batch, kv_lo, kv_hi, reps, sched, tile_m):
     """The step is deterministic by construction (fixed reduction orders, last-arriver merges in
     index order): repeating it on the same inputs must give the same bits every time.  A
     hand-off between XCDs that sometimes delivers a stale activation row shows up here as a row
     that differs in a few steps out of a hundred, while staying inside the parity tolerance."""
     c = _case(weights, batch, kv_lo, kv_hi, seed=3, rows=[0])
     sh, B = c["shape"], batch
-    f = F.fleet_create(sh.asdict(), c["w"], 0, 0, 0)
+    f = F.fleet_create(sh.asdict(), c["w"], sched, tile_m, 0)
     try:
         kc, vc = c["kc"].clone(), c["vc"].clone()
         stream = torch.cuda.current_stream().cuda_stream
@@ -179,5 +181,42 @@ def test_repeated_steps_give_identical_bits(weights, batch, kv_lo, kv_hi, reps):
             if not (same_h and same_l):
                 rows = torch.nonzero((hout - first[0]).abs().amax(1)).flatten().tolist()
                 raise AssertionError(f"step {r} differs from step 0 in batch rows {rows}")
+    finally:
+        F.fleet_destroy(f)
+
+
+@pytest.mark.parametrize("batch", [1, 8])
+def test_repeated_multi_step_launches_give_identical_bits(weights, batch):
+    """Several greedy steps in one launch (the kernel walks its queues once per step, the
+    counters keep growing, the next token and position come from the device): the same
+    launch repeated from the same state gives the same tokens, logits and cache entries."""
+    n_tokens, reps = 8, 25
+    w, wh = weights
+    shape = si.qwen3_8b_shape(max_batch=batch, max_seq=1100, n_layers=L)
+    g = si.Gen(5, "cuda")
+    kc0, vc0 = si.make_kv_cache(shape, g)
+    embed = g.normal_bf16((shape.vocab, shape.hidden), 1.0)
+    tok0 = g.randint(0, shape.vocab - 1, batch)
+    pos0 = g.randint(900, 1000, batch)
+    f = F.fleet_create(shape.asdict(), {**w, "embed": embed}, 0, 0, 0)
+    try:
+        first = None
+        for r in range(reps):
+            kc, vc = kc0.clone(), vc0.clone()
+            tok, pos = tok0.clone(), pos0.clone()
+            out = torch.full((n_tokens, batch), -1, device="cuda", dtype=torch.int32)
+            hout = torch.zeros((batch, shape.hidden), device="cuda")
+            logits = torch.zeros((batch, shape.vocab), device="cuda")
+            F.fleet_decode_tokens(f, batch, tok, kc, vc, pos, n_tokens, out, hout, logits)
+            torch.cuda.synchronize()
+            assert F.fleet_last_status(f)["code"] == 0
+            new_k = torch.stack([kc[:, b, :, int(pos0[b]):int(pos0[b]) + n_tokens] for b in range(batch)])
+            cur = (out.clone(), logits.view(torch.int32).clone(), hout.view(torch.int32).clone(), new_k.view(torch.int16).clone())
+            if first is None:
+                first = cur
+                assert (out >= 0).all() and torch.equal(pos, pos0 + n_tokens)
+                continue
+            for nm, a, b_ in zip(("tokens", "logits", "hidden", "new keys"), cur, first):
+                assert torch.equal(a, b_), f"launch {r}: {nm} differ from launch 0"
     finally:
         F.fleet_destroy(f)
