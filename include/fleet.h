@@ -150,6 +150,8 @@ int fleet_create(const fleet_shape_t *shape, const fleet_weights_t *weights, fle
  *              the step); not advanced by the library
  *   hidden_out device fp32 [batch, hidden]: residual stream after the last layer
  *   logits     device fp32 [batch, vocab], or NULL
+ * hidden_in, the caches, hidden_out and logits must be 16-byte aligned (FLEET_EINVAL
+ * otherwise): the kernels move them in 16-byte pieces.
  * The first call for a given batch size builds and uploads that batch's task
  * graph (host work + one device allocation); later calls only launch.
  * A dependency wait that times out aborts the step on the device; the next

@@ -332,6 +332,11 @@ int run_layers(fleet* f, int batch, int layer_begin, int layer_end, bool with_in
                const void* hidden_in, const int32_t* tokens, void* k_cache, void* v_cache, const int32_t* positions,
                float* hidden_out, float* logits, hipStream_t st, int n_tokens = 0, int32_t* tokens_out = nullptr,
                const KvPaging* paging = nullptr) {
+  // the kernels move activations, cache rows and logits in 16-byte pieces
+  for (const void* p : {hidden_in, (const void*)k_cache, (const void*)v_cache, (const void*)hidden_out, (const void*)logits})
+    if ((uintptr_t)p % 16 != 0) return FLEET_EINVAL;
+  for (const void* p : {(const void*)tokens, (const void*)positions, (const void*)tokens_out, paging ? (const void*)paging->table : nullptr})
+    if ((uintptr_t)p % 4 != 0) return FLEET_EINVAL;
   DevGraph* dg = nullptr;
   int rc = get_graph(f, batch, &dg, n_tokens > 0);
   if (rc) return rc;

@@ -109,6 +109,29 @@ def test_attention_scores_of_wide_range(batch, ramp):
         check_new_kv(m, got[2], got[3], k, v)
 
 
+def test_misaligned_buffers_are_rejected():
+    """Outputs are written in 16-byte pieces: a logits or hidden_out pointer that is not
+    16-byte aligned is refused on the host before anything is launched."""
+    sh = si.reduced_shape(max_batch=2, max_seq=40, n_layers=1, vocab=512)
+    m = Model(sh, seed=6, batch=2, positions=[3, 17])
+    f = F.fleet_create(sh.asdict(), m.w, 0, 0, 0)
+    try:
+        kc, vc = m.kc.clone(), m.vc.clone()
+        hout = torch.zeros(2 * sh.hidden + 4, device="cuda")
+        logits = torch.zeros(2 * sh.vocab + 4, device="cuda")
+        stream = torch.cuda.current_stream().cuda_stream
+        for ho, lg in ((hout[1:1 + 2 * sh.hidden], logits[:2 * sh.vocab]), (hout[:2 * sh.hidden], logits[1:1 + 2 * sh.vocab])):
+            with pytest.raises(F.FleetError):
+                F.fleet_decode_step(f, 2, m.hidden, None, kc, vc, m.pos, ho, lg, stream)
+        F.fleet_decode_step(f, 2, m.hidden, None, kc, vc, m.pos, hout[4:4 + 2 * sh.hidden], logits[4:4 + 2 * sh.vocab], stream)
+        assert F.fleet_last_status(f)["code"] == 0
+        (ho_ref, lg_ref), _, _ = m.run_oracle()
+        assert_close(hout[4:4 + 2 * sh.hidden].reshape(2, -1).cpu().numpy(), ho_ref, "hidden_out")
+        assert_close(logits[4:4 + 2 * sh.vocab].reshape(2, -1).cpu().numpy(), lg_ref, "logits")
+    finally:
+        F.fleet_destroy(f)
+
+
 def test_one_fleet_many_batch_sizes():
     """One fleet_t serves steps of different batch sizes in any order (a graph per batch size,
     built on first use and cached; shared scratch activations and counters): every step equals
