@@ -232,9 +232,9 @@ static MfmaPlan plan_for(int sched, int flags, int n_units, int K, int nb, int t
 }
 
 // Largest batch that runs the FMA GEMV kernels.  Measured on MI355X the MFMA kernels win from
-// batch 3 on (per step: batch 2 3.50 ms FMA / 3.70 ms MFMA, batch 3 4.14 / 3.86, batch 4
-// 4.23 / 3.87, batch 8 6.4 / 4.1), so the default is 2; the environment variable
-// FLEET_FMA_MAX_BATCH (0..8) moves the switch, e.g. to 8 for FMA at batch 3-8.
+// batch 3 on (per step: batch 2 3.77 ms with either, batch 3 4.41 ms FMA / 3.80 ms MFMA, batch 4
+// 4.58 / 3.78), so the default is 2; the environment variable FLEET_FMA_MAX_BATCH (0..8) moves
+// the switch, e.g. to 8 for FMA at batch 3-8.
 static int fma_max() {
   const char* e = getenv("FLEET_FMA_MAX_BATCH");
   if (!e) return 2;
