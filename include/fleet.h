@@ -10,8 +10,9 @@
  * (XCD-local, then device) signalling.
  *
  * Conventions
- *   - every function returns 0 (FLEET_OK) or a negative fleet_err code; nothing
- *     throws or aborts.  fleet_strerror() names a code.
+ *   - every function that returns int returns 0 (FLEET_OK) or a negative fleet_err code;
+ *     nothing throws or aborts (the closed-form helpers return -1 or 0.0 for a
+ *     non-positive divisor).  fleet_strerror() names a code.
  *   - "device" pointers are HIP device memory of the current device, "host"
  *     pointers are ordinary host memory.  The library never takes ownership of
  *     a caller buffer.
@@ -69,24 +70,30 @@ enum fleet_flags {
   FLEET_FLAG_UNFUSED_SILU = 256,/* gate|up GEMM stores its fp32 sums; SiLU(gate) x up runs as
                                   a stage of CU-tasks of its own (section 3.2, operator
                                   fusion ablation)                                      */
-  FLEET_FLAG_LEADER_RELAY = 512 /* only the leader (rank 0) of an XCD polls the device counter
+  FLEET_FLAG_LEADER_RELAY = 512,/* only the leader (rank 0) of an XCD polls the device counter
                                   and relays it to a word per follower, instead of every
                                   worker polling one of the per-XCD copies of the counter */
+  FLEET_FLAG_PACKED_ONLY = 1024 /* every batch size runs the MFMA kernels on the library's
+                                  packed weight copy: the caller may free wqkv, wo, wgu, wdown
+                                  and lm_head once fleet_create has returned (one copy of
+                                  the GEMM weights in device memory instead of two)     */
 };
 
 typedef struct {
   int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn;
   int32_t vocab;      /* 0: no final norm / LM head                                     */
-  int32_t max_batch;  /* 1..64                                                           */
+  int32_t max_batch;  /* 1..128 (max_batch * n_kv_heads <= 1024)                         */
   int32_t max_seq;    /* KV slots per sequence; positions[b] < max_seq                   */
   float rms_eps;      /* 1e-6                                                            */
   float rope_theta;   /* 1e6                                                             */
   int32_t sched_mode; /* enum fleet_sched                                                */
   int32_t tile_m;     /* GEMM tile height along the batch on the MFMA path: 16, 32, 64, or
                          0 = whole batch rounded up to 16 (reads each weight once).
+                         Batches above 64 use 64-row tiles (0) or the given height.
                          Batches up to 2 run FMA GEMV kernels, larger ones bf16 MFMA
                          kernels; the environment variable FLEET_FMA_MAX_BATCH (0..8),
-                         read when a graph is built, moves that switch                  */
+                         read once by fleet_create (and by fleet_gemm and
+                         fleet_graph_build per call), moves that switch                 */
   int32_t flags;      /* enum fleet_flags                                                */
 } fleet_shape_t;
 
@@ -123,17 +130,24 @@ typedef struct {
 } fleet_status_t;
 
 /*
- * fleet_create: validate the shape, probe the device (CU count, XCD count),
- * allocate descriptors, counters and scratch activations, build the RoPE table, and
- * (max_batch on the MFMA path) repack the GEMM weights into a private copy.
- * Paper section 4.3 (task registration at model load).  *out is set on success.
- * Device memory the library owns besides that copy: the activations of one step
- * (a few MB), and, on the MFMA path, the partial sums of split-K GEMM tiles: 8 k-slices x
- * 64 rows x the widest GEMM output, fp32, once per XCD under the XCD-aware schedules
- * (8 x 50 MB for the Qwen3-8B shape).
- * Requirements: head_dim == 128, hidden/ffn/(nq*head_dim) multiples of 16,
- * n_q_heads a multiple of n_kv_heads with ratio <= 4, vocab a multiple of 16,
- * hidden and ffn multiples of 32.
+ * fleet_create: validate the shape, probe the device (CU count, XCD count), repack the
+ * GEMM weights into a private copy (max_batch on the MFMA path), build and upload the task
+ * graph of every batch bucket (powers of two up to max_batch, and max_batch itself; with
+ * vocab > 0 and embed also the graphs of fleet_decode_tokens), allocate the working memory
+ * of one step, and build the RoPE table.  Paper section 4.3 (task registration at model
+ * load).  *out is set on success; on failure everything allocated so far is freed.
+ * Everything a step needs exists afterwards: the step calls allocate and copy nothing, and
+ * a step of any batch <= max_batch runs the graph of the smallest bucket that holds it (the
+ * tasks of the rows it does not have only follow their events; paper section 2.3: no
+ * graph per batch size has to be captured on the way).
+ * Device memory the library owns besides the packed copy: the descriptors of the graphs (a
+ * few MB each), the activations of one step (a few MB), and, on the MFMA path, the partial
+ * sums of split-K GEMM tiles: k-slices x padded batch x the widest split output, fp32, once
+ * per XCD under the XCD-aware schedules (8 x 8 MB for the Qwen3-8B shape at batch 64).
+ * Requirements: head_dim == 128, n_q_heads a multiple of n_kv_heads with ratio <= 4, vocab
+ * a multiple of 16, hidden and ffn multiples of 32; every weight matrix smaller than 2 GiB
+ * and max_seq * 256 < 2^31 (the kernels use 32-bit byte offsets inside a matrix and inside
+ * one (sequence, kv head) stream of the cache).  Anything else: FLEET_EINVAL.
  */
 int fleet_create(const fleet_shape_t *shape, const fleet_weights_t *weights, fleet_t **out);
 
@@ -149,11 +163,12 @@ int fleet_create(const fleet_shape_t *shape, const fleet_weights_t *weights, fle
  *   positions  device int32 [batch]: index of the new token (= valid slots before
  *              the step); not advanced by the library
  *   hidden_out device fp32 [batch, hidden]: residual stream after the last layer
- *   logits     device fp32 [batch, vocab], or NULL
+ *   logits     device fp32 [batch, vocab], or NULL: the step then ends after the last
+ *              layer and the final norm (no LM head)
  * hidden_in, the caches, hidden_out and logits must be 16-byte aligned (FLEET_EINVAL
  * otherwise): the kernels move them in 16-byte pieces.
- * The first call for a given batch size builds and uploads that batch's task
- * graph (host work + one device allocation); later calls only launch.
+ * The call launches two kernels on `stream` and does nothing else: no allocation, no
+ * copy, no synchronisation (it can be captured into a HIP graph).
  * A dependency wait that times out aborts the step on the device; the next
  * fleet_last_status() reports FLEET_ETIMEOUT.
  * The result is a function of the inputs alone: every reduction has a fixed order, so
@@ -177,6 +192,7 @@ int fleet_decode_layers(fleet_t *f, int32_t batch, int32_t layer_begin, int32_t 
 
 /* fleet_destroy: free everything the library allocated.  NULL is accepted. */
 int fleet_destroy(fleet_t *f);
+
 
 /*
  * fleet_decode_step_paged: fleet_decode_step over a paged KV cache.
@@ -226,7 +242,7 @@ int fleet_decode_tokens(fleet_t *f, int32_t batch, int32_t *tokens, void *k_cach
  *   sched_mode, tile_m  as in fleet_shape_t
  *   elapsed_ms  HOST float or NULL: time of the one kernel launch that runs all
  *             reps, measured with HIP events on `stream`
- * K a multiple of 32, N of 16, 1 <= B <= 64.  Synchronous: returns after the
+ * K a multiple of 32, N of 16, N * K * 2 < 2^31, 1 <= B <= 128.  Synchronous: returns after the
  * kernel has finished (it allocates and frees its own descriptors and, on the MFMA
  * path, packed copies of x and of every weight copy).  Repetitions are independent
  * of each other unless FLEET_FLAG_CHAINED is set; with a split-K plan a repetition
@@ -240,7 +256,7 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void *x, const void *const
  * fleet_graph_build (host only, no device needed): the task graph the library
  * would run for `batch` on a device with n_xcd chiplets, as int32 words:
  *   header[32], ops[n_ops][16], tasks[n_tasks][16], events[n_events][4],
- *   queue offsets[n_xcd + 1], queue entries[n_qent][4], layer marks[n_xcd][n_layers + 3],
+ *   queue offsets[n_xcd + 1], queue entries[n_qent][4], layer marks[n_xcd][n_layers + 4],
  *   residual-ready events[n_layers + 1]
  * (word meanings documented in csrc/graph.hpp).  buf may be NULL to query the size; *len is
  * in/out in bytes.  Paper sections 3.1 (task scopes, events), 3.2 (partitioning,
@@ -249,7 +265,8 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void *x, const void *const
 int fleet_graph_build(const fleet_shape_t *shape, int32_t batch, int32_t n_xcd,
                       int32_t n_workers, void *buf, size_t *len);
 
-/* fleet_graph_dump: the same words for the graph `f` runs at `batch`. */
+/* fleet_graph_dump: the same words for the graph `f` runs at `batch`: the graph of the
+ * smallest batch bucket that holds `batch` (header word "batch" names the bucket). */
 int fleet_graph_dump(fleet_t *f, int32_t batch, void *buf, size_t *len);
 
 /*

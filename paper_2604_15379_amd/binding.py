@@ -18,6 +18,7 @@ _LIB_PATH = os.path.join(_PKG, "libfleet.so")
 SCHED_COOPERATIVE, SCHED_UNAWARE, SCHED_MSPLIT = 0, 1, 2
 FLAG_TRACE, FLAG_SINGLE_LEVEL, FLAG_SEPARATE_NORM, FLAG_CHAINED, FLAG_TIMING = 1, 2, 4, 8, 16
 FLAG_NO_SPLITK, FLAG_NO_STREAM, FLAG_NO_RESIDENT, FLAG_UNFUSED_SILU, FLAG_LEADER_RELAY = 32, 64, 128, 256, 512
+FLAG_PACKED_ONLY = 1024
 
 EXPORTS = (
     "fleet_create", "fleet_decode_step", "fleet_decode_step_paged", "fleet_decode_layers",
@@ -291,7 +292,7 @@ def parse_graph(words: np.ndarray) -> dict:
     events = w[o:o + h["n_events"] * EVENT_WORDS].reshape(-1, EVENT_WORDS); o += events.size
     qoff = w[o:o + h["n_xcd"] + 1]; o += qoff.size
     qents = w[o:o + h["n_qent"] * QENT_WORDS].reshape(-1, QENT_WORDS); o += qents.size
-    n_marks = h["n_layers"] + 3
+    n_marks = h["n_layers"] + 4
     marks = w[o:o + h["n_xcd"] * n_marks].reshape(h["n_xcd"], n_marks); o += marks.size
     xready = w[o:]
     return dict(header=h, ops=ops, tasks=tasks, events=events, qoff=qoff, qents=qents,

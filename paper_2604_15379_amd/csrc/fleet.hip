@@ -2,12 +2,13 @@
 // allocation, graph upload and the per-step launch of the persistent kernel.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
-#include <map>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -15,33 +16,44 @@
 #include "graph.hpp"
 #include "kernels.hip.inc"
 
+
 namespace {
 
 using namespace fleetg;
 
 constexpr size_t LDS_BYTES = 128 * 1024;  // > half of a CU's 160 KB: one worker per CU
 constexpr int TRACE_CAP = 2048;           // records per worker
+constexpr int MAX_DEVICES = 64;
 
 struct DevInfo {
   int n_cu = 0, n_xcd = 0;
   int per_xcd[dev::MAX_XCD] = {0};
 };
 
+// Device memory one launch works in besides the caller's buffers and the graph's
+// descriptors: activations, partial sums, the counter block and the status block, carved
+// from one base (the fleet's own allocation, or the static workspace).
+struct Work {
+  float* x = nullptr; void* n = nullptr; float* qkv = nullptr; void* att = nullptr; void* h = nullptr;
+  float* part = nullptr; float* gpart = nullptr; float* gu32 = nullptr;
+  uint32_t* ctr = nullptr; int32_t* status = nullptr;
+  size_t gpart_region = 0;   // bytes between the per-XCD regions of gpart
+};
+
 struct DevGraph {
   Graph g;
   int32_t *ops = nullptr, *tasks = nullptr, *events = nullptr, *qoff = nullptr, *qents = nullptr;
   int32_t* fat = nullptr;   // [n_tasks][FAT_WORDS]: task words, op words, weight pointers, id
-  uint32_t* ctr = nullptr;
   int ctr_words = 0, gcnt_base = 0;
   // memo of wait_event_range for the last queue slice launched
   int memo_begin[dev::MAX_XCD] = {-1, -1, -1, -1, -1, -1, -1, -1}, memo_end[dev::MAX_XCD] = {0}, memo_first = 0, memo_last = -1;
   ~DevGraph() {
-    for (void* p : {(void*)ops, (void*)tasks, (void*)events, (void*)qoff, (void*)qents, (void*)fat, (void*)ctr})
+    for (void* p : {(void*)ops, (void*)tasks, (void*)events, (void*)qoff, (void*)qents, (void*)fat})
       if (p) (void)hipFree(p);
   }
 };
 
-int g_last_hip = 0;
+thread_local int g_last_hip = 0;
 #define HIP_TRY(expr)                              \
   do {                                             \
     hipError_t e_ = (expr);                        \
@@ -101,7 +113,6 @@ int variant_for(int path, int batch, int tile_m) {
 // range of events that tasks of the launched queue slices wait for (stages of the slices)
 void wait_event_range(const Graph& g, dev::Params& P, int n_xcd) {
   int lo = 1 << 30, hi = -1;
-  std::vector<char> stage_in;
   for (int x = 0; x < n_xcd; ++x)
     for (int qi = P.q_begin[x]; qi < P.q_end[x]; ++qi) {
       const int32_t* e = &g.qents[((size_t)g.qoff[x] + qi) * QENT_WORDS];
@@ -132,11 +143,16 @@ int launch_persistent(DevGraph* dg, dev::Params& P, int n_cu, hipStream_t st) {
   return FLEET_OK;
 }
 
+// Per-device, once: raise the kernels' dynamic LDS limit and check that one worker fits a CU.
+std::mutex g_dev_mutex;
+bool g_prepared[MAX_DEVICES] = {false};
+
 int prepare_kernel() {
-  static bool done = false;
-  if (done) return FLEET_OK;
   int dev_id = 0, lds = 0;
   HIP_TRY(hipGetDevice(&dev_id));
+  if (dev_id < 0 || dev_id >= MAX_DEVICES) return FLEET_EDEVICE;
+  std::lock_guard<std::mutex> lock(g_dev_mutex);
+  if (g_prepared[dev_id]) return FLEET_OK;
   HIP_TRY(hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev_id));
   if ((size_t)lds < LDS_BYTES + 4096) return FLEET_EDEVICE;
   for (int v = 0; v < dev::N_VARIANTS; ++v) {
@@ -147,9 +163,10 @@ int prepare_kernel() {
   int per_cu = 0;
   HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fleet_persistent_kernel<6>, dev::WG, LDS_BYTES));
   if (per_cu < 1) return FLEET_EDEVICE;
-  done = true;
+  g_prepared[dev_id] = true;
   return FLEET_OK;
 }
+
 
 int probe_device(DevInfo* info, int32_t* xcd_of_block_out, int n_blocks_req) {
   int rc = prepare_kernel();
@@ -185,10 +202,14 @@ long long timeout_ticks_from_env() {
   return (long long)(ms * 1e5);   // 100 MHz
 }
 
+constexpr size_t WORK_ALIGN = 256;
+size_t align_up(size_t v) { return (v + WORK_ALIGN - 1) / WORK_ALIGN * WORK_ALIGN; }
+
 }  // namespace
 
 struct fleet {
   fleet_shape_t shape;
+  int fma_max = 2;   // largest batch on the FMA GEMV path, latched at create
   std::vector<const void*> ln1, wqkv, q_norm, k_norm, wo, ln2, wgu, wdown;
   const void *embed = nullptr, *final_norm = nullptr, *lm_head = nullptr;
   // library-owned copies of the GEMM weights in the operand-block layout of the MFMA
@@ -196,46 +217,102 @@ struct fleet {
   std::vector<void*> pk_qkv, pk_o, pk_gu, pk_down;
   void* pk_lm = nullptr;
   DevInfo info;
-  // scratch activations (device)
-  float* x = nullptr; void* n = nullptr; float* qkv = nullptr; void* att = nullptr; void* h = nullptr;
-  float* part = nullptr; float* gpart = nullptr; float* gu32 = nullptr; float2* rope = nullptr;
-  size_t gpart_bytes = 0;   // bytes of one region of gpart
-  int32_t* status = nullptr; int32_t* trace = nullptr;
-  std::map<int, std::unique_ptr<DevGraph>> graphs;        // by batch size
-  std::map<int, std::unique_ptr<DevGraph>> graphs_loop;   // with the next-token stage (multi-step launches)
+  // one graph per batch bucket, built and uploaded by fleet_create: a step of `batch`
+  // sequences runs the graph of the smallest bucket that holds it
+  std::vector<int> buckets;
+  std::vector<std::unique_ptr<DevGraph>> graphs;        // by bucket
+  std::vector<std::unique_ptr<DevGraph>> graphs_loop;   // with the next-token stage (multi-step launches)
+  char* work = nullptr;      // the fleet's own working memory (layout: work_layout())
+  size_t work_bytes = 0;
+  float2* rope = nullptr;
+  int32_t* trace = nullptr;
   long long timeout_ticks = 0;
-  int last_code = 0;
-  DevGraph* last_graph = nullptr;
+  int32_t* last_status = nullptr;   // status block of the last launch (device)
+  float* last_x = nullptr;          // residual stream of the last launch (device)
+
+  ~fleet() {
+    for (void* p : {(void*)work, (void*)rope, (void*)trace})
+      if (p) (void)hipFree(p);
+    for (auto* v : {&pk_qkv, &pk_o, &pk_gu, &pk_down})
+      for (void* p : *v) if (p) (void)hipFree(p);
+    if (pk_lm) (void)hipFree(pk_lm);
+  }
 };
 
 namespace {
 
-const void* resolve_weight(const fleet* f, int wkind, int layer, const void* const* gemm_copies, const void** second,
-                           bool packed = false) {
-  *second = nullptr;
+// Working memory of one launch of graph dg, carved from `base` (may be null: sizes only).
+// Returns the bytes needed.
+size_t work_layout(const fleet* f, const DevGraph* dg, char* base, Work* w) {
+  const Graph& g = dg->g;
+  const fleet_shape_t& s = f->shape;
+  const size_t B = g.header[H_BATCH], B16 = (B + 15) / 16 * 16, H = s.hidden, F = s.ffn;
+  const size_t NQKV = (size_t)(s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim, QD = (size_t)s.n_q_heads * s.head_dim;
+  const size_t grp = s.n_q_heads / s.n_kv_heads, S = std::max(1, g.header[H_N_SPLITS]);
+  auto pad256 = [](size_t k) { return (k + 255) / 256 * 256; };
+  // partial sums of the graph's split-K operators: [k-slice][unit][m-tile][blocks x 256] fp32
+  size_t gp = 0;
+  for (int i = 0; i < g.n_ops(); ++i) {
+    const int32_t* o = &g.ops[(size_t)i * OP_WORDS];
+    if (o[O_BODY] != B_GEMM || o[O_PATH] != P_MFMA) continue;
+    const size_t ks = std::max(1, (o[O_AUX2] >> 16) & 15), nb = o[O_EPI] == E_SWIGLU_BF16 ? 2 : 1;
+    if (ks > 1) gp = std::max(gp, ks * nb * (size_t)o[O_N_UNITS] * o[O_M_TILES] * mfma_blocks(o[O_TILE_M]) * 256 * 4);
+  }
+  gp = align_up(gp);
+  const size_t regions = s.sched_mode == FLEET_SCHED_UNAWARE ? 1 : dev::MAX_XCD;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { char* p = base ? base + off : nullptr; off += align_up(bytes); return p; };
+  char* x = take(B * H * 4);
+  char* n = take(B16 * pad256(H) * 2);       // bf16 activations: operand blocks of 16 rows on the MFMA path
+  char* qkv = take(B * NQKV * 4);
+  char* att = take(B16 * pad256(QD) * 2);
+  char* h = take(B16 * pad256(F) * 2);
+  char* part = take(B * s.n_kv_heads * S * grp * dev::PART_STRIDE * 4);
+  char* gpart = take(gp * regions);
+  char* gu32 = take((s.flags & FLEET_FLAG_UNFUSED_SILU) ? B * 2 * F * 4 : 0);
+  char* ctr = take((size_t)dg->ctr_words * 4);
+  char* status = take(dev::ST_WORDS * 4);
+  if (w) {
+    w->x = (float*)x; w->n = n; w->qkv = (float*)qkv; w->att = att; w->h = h; w->part = (float*)part;
+    w->gpart = (float*)gpart; w->gu32 = (float*)gu32; w->ctr = (uint32_t*)ctr; w->status = (int32_t*)status;
+    w->gpart_region = gp;
+  }
+  return off;
+}
+
+int resolve_weight(const fleet* f, int wkind, int layer, const void* const* gemm_copies, bool packed,
+                   const void** first, const void** second) {
+  *first = *second = nullptr;
   if (packed && f) {
+    const std::vector<void*>* v = nullptr;
     switch (wkind) {
-      case W_QKV: return f->pk_qkv[layer];
-      case W_O: return f->pk_o[layer];
-      case W_GU: return f->pk_gu[layer];
-      case W_DOWN: return f->pk_down[layer];
-      case W_LM: return f->pk_lm;
+      case W_QKV: v = &f->pk_qkv; break;
+      case W_O: v = &f->pk_o; break;
+      case W_GU: v = &f->pk_gu; break;
+      case W_DOWN: v = &f->pk_down; break;
+      case W_LM: if (!f->pk_lm) return FLEET_EINVAL; *first = f->pk_lm; return FLEET_OK;
       default: break;
+    }
+    if (v) {   // an MFMA graph needs the packed copies fleet_create makes
+      if ((size_t)layer >= v->size() || !(*v)[layer]) return FLEET_EINVAL;
+      *first = (*v)[layer];
+      return FLEET_OK;
     }
   }
   switch (wkind) {
-    case W_QKV: return f->wqkv[layer];
-    case W_O: return f->wo[layer];
-    case W_GU: return f->wgu[layer];
-    case W_DOWN: return f->wdown[layer];
-    case W_LM: return f->lm_head;
-    case W_LN1: return f->ln1[layer];
-    case W_LN2: return f->ln2[layer];
-    case W_FINAL: return f->final_norm;
-    case W_EMBED: *second = f->embed; return nullptr;
-    case W_GEMM_COPY: return gemm_copies ? gemm_copies[layer] : nullptr;
-    default: return nullptr;
+    case W_QKV: *first = f->wqkv[layer]; break;
+    case W_O: *first = f->wo[layer]; break;
+    case W_GU: *first = f->wgu[layer]; break;
+    case W_DOWN: *first = f->wdown[layer]; break;
+    case W_LM: *first = f->lm_head; break;
+    case W_LN1: *first = f->ln1[layer]; break;
+    case W_LN2: *first = f->ln2[layer]; break;
+    case W_FINAL: *first = f->final_norm; break;
+    case W_EMBED: *second = f->embed; break;
+    case W_GEMM_COPY: *first = gemm_copies ? gemm_copies[layer] : nullptr; break;
+    default: break;
   }
+  return FLEET_OK;
 }
 
 int upload_graph(DevGraph* dg, const fleet* f, const void* const* gemm_copies, int n_xcd) {
@@ -250,13 +327,14 @@ int upload_graph(DevGraph* dg, const fleet* f, const void* const* gemm_copies, i
   for (int i = 0; i < g.n_ops(); ++i) {
     const int32_t* o = &g.ops[(size_t)i * OP_WORDS];
     if (o[O_BODY] == B_ATTN && f) { w[i] = f->q_norm[o[O_LAYER]]; w2[i] = f->k_norm[o[O_LAYER]]; continue; }
-    const void* second = nullptr;
-    w[i] = f || gemm_copies ? resolve_weight(f, o[O_WKIND], o[O_LAYER], gemm_copies, &second, o[O_PATH] == P_MFMA) : nullptr;
-    if (o[O_BODY] == B_GEMM && (o[O_AUX2] & 0xff) != W_NONE && f) {   // gain of the fused RMSNorm
+    if (!f && !gemm_copies) continue;
+    const void *first = nullptr, *second = nullptr;
+    if ((rc = resolve_weight(f, o[O_WKIND], o[O_LAYER], gemm_copies, o[O_PATH] == P_MFMA, &first, &second))) return rc;
+    if (o[O_BODY] == B_GEMM && (o[O_AUX2] & 0xff) != W_NONE && f) {   // gain of the fused RMSNorm, or the matrix to warm
       const void* unused = nullptr;
-      second = resolve_weight(f, o[O_AUX2] & 0xff, o[O_LAYER], nullptr, &unused);
+      if ((rc = resolve_weight(f, o[O_AUX2] & 0xff, o[O_LAYER], nullptr, false, &second, &unused))) return rc;
     }
-    w2[i] = second;
+    w[i] = first; w2[i] = second;
   }
   // one self-contained descriptor per task, so that a worker fetches it with one read
   std::vector<int32_t> fat((size_t)g.n_tasks() * dev::FAT_WORDS, 0);
@@ -277,18 +355,17 @@ int upload_graph(DevGraph* dg, const fleet* f, const void* const* gemm_copies, i
       for (int t = e[Q_FIRST]; t < e[Q_FIRST] + e[Q_COUNT]; ++t) fat[(size_t)t * dev::FAT_WORDS + dev::FAT_GROUP] = e[Q_COUNT];
     }
   if ((rc = upload(&dg->fat, fat.data(), fat.size() * 4))) return rc;
-  // G[e], L[x][e], then one arrival counter per (sequence, kv head) for the split-KV merge
-  // and one relay word per worker on its own cache line
-  // (MFMA graphs: then the arrival counters of split-K GEMM tiles)
-  // (then one copy of the device counters per XCD, rows on their own cache lines)
+  // counter block: G[e], L[x][e], one arrival counter per (sequence, kv head) for the split-KV
+  // merge, one relay word per worker on its own cache line, the per-XCD copies of the device
+  // counters (rows on their own cache lines), and (MFMA graphs) the arrival counters of
+  // split-K GEMM tiles
   dg->gcnt_base = dev::C_EVENTS + g.n_events() * (1 + n_xcd) + dev::N_PAIR + n_xcd * dev::RELAY_SLOTS * dev::RELAY_STRIDE +
                   dev::COPY_GROUPS * n_xcd * ((g.n_events() + 31) & ~31);
   dg->ctr_words = dg->gcnt_base + (g.header[H_PATH] == P_MFMA ? dev::GEMM_CNT_WORDS : 0);
-  if ((rc = upload(&dg->ctr, nullptr, (size_t)dg->ctr_words * 4))) return rc;
   return FLEET_OK;
 }
 
-// reset counters, then run queue slice [q_begin, q_end) of every XCD
+// reset counters and status, then run queue slice [q_begin, q_end) of every XCD
 int launch(dev::Params& P, DevGraph* dg, int n_cu, int preset_event, hipStream_t st) {
   const int words = dg->ctr_words;
   int preset_word = -1;
@@ -299,80 +376,95 @@ int launch(dev::Params& P, DevGraph* dg, int n_cu, int preset_event, hipStream_t
   }
   const int nE = dg->g.n_events(), nx = dg->g.header[H_N_XCD], cstride = (nE + 31) & ~31;
   const int cbase = dev::C_EVENTS + nE * (1 + nx) + dev::N_PAIR + nx * dev::RELAY_SLOTS * dev::RELAY_STRIDE;
-  hipLaunchKernelGGL(fleet_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, st, dg->ctr, words, preset_word,
+  hipLaunchKernelGGL(fleet_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, st, P.ctr, words, preset_word,
                      preset_val, P.status, cbase, cstride, dev::COPY_GROUPS * nx, preset_event);
   return launch_persistent(dg, P, n_cu, st);
 }
 
 void fill_graph_params(dev::Params& P, const DevGraph* dg) {
   P.ops = dg->ops; P.tasks = dg->tasks; P.events = dg->events; P.qoff = dg->qoff; P.qents = dg->qents;
-  P.fat = dg->fat; P.ctr = dg->ctr; P.n_events = dg->g.n_events(); P.gcnt_base = dg->gcnt_base;
+  P.fat = dg->fat; P.n_events = dg->g.n_events(); P.gcnt_base = dg->gcnt_base;
 }
 
-int get_graph(fleet* f, int batch, DevGraph** out, bool loop = false) {
-  auto& cache = loop ? f->graphs_loop : f->graphs;
-  auto it = cache.find(batch);
-  if (it != cache.end()) { *out = it->second.get(); return FLEET_OK; }
-  std::unique_ptr<DevGraph> dg(new (std::nothrow) DevGraph());
-  if (!dg) return FLEET_ENOMEM;
-  dg->g = build_decode_graph(f->shape, batch, f->info.n_xcd, f->info.n_cu, loop);
-  int rc = upload_graph(dg.get(), f, nullptr, f->info.n_xcd);
-  if (rc) return rc;
-  *out = dg.get();
-  cache[batch] = std::move(dg);
-  return FLEET_OK;
+// the graph that serves a step of `batch` sequences: the smallest bucket that holds it
+DevGraph* pick_graph(fleet* f, int batch, bool loop) {
+  auto& set = loop ? f->graphs_loop : f->graphs;
+  for (size_t i = 0; i < f->buckets.size() && i < set.size(); ++i)
+    if (f->buckets[i] >= batch) return set[i].get();
+  return nullptr;
 }
+
 struct KvPaging {   // paged KV cache: k_cache / v_cache are page pools
   const int32_t* table = nullptr;   // device [batch][stride] page indices
   int page_size = 0, n_pages = 0, stride = 0;
 };
 
-// n_tokens > 0: the whole step n_tokens times in one launch (graph with the next-token stage)
-int run_layers(fleet* f, int batch, int layer_begin, int layer_end, bool with_ingest, bool with_final,
-               const void* hidden_in, const int32_t* tokens, void* k_cache, void* v_cache, const int32_t* positions,
-               float* hidden_out, float* logits, hipStream_t st, int n_tokens = 0, int32_t* tokens_out = nullptr,
-               const KvPaging* paging = nullptr) {
+struct StepArgs {
+  int batch = 0, layer_begin = 0, layer_end = 0;
+  bool with_ingest = false, with_final = false;
+  const void* hidden_in = nullptr; const int32_t* tokens = nullptr;
+  void *k_cache = nullptr, *v_cache = nullptr; const int32_t* positions = nullptr;
+  float *hidden_out = nullptr, *logits = nullptr;
+  int n_tokens = 0; int32_t* tokens_out = nullptr;   // n_tokens > 0: that many steps in one launch
+  const KvPaging* paging = nullptr;
+  const float* x_in = nullptr;                       // layer ranges: residual stream to start from
+};
+
+// No allocation, no host-device copy, no synchronisation: kernels (and, for layer ranges,
+// device-to-device copies) on the stream only.
+int run_layers(fleet* f, const StepArgs& a, hipStream_t st) {
   // the kernels move activations, cache rows and logits in 16-byte pieces
-  for (const void* p : {hidden_in, (const void*)k_cache, (const void*)v_cache, (const void*)hidden_out, (const void*)logits})
+  for (const void* p : {a.hidden_in, (const void*)a.k_cache, (const void*)a.v_cache, (const void*)a.hidden_out, (const void*)a.logits})
     if ((uintptr_t)p % 16 != 0) return FLEET_EINVAL;
-  for (const void* p : {(const void*)tokens, (const void*)positions, (const void*)tokens_out, paging ? (const void*)paging->table : nullptr})
+  for (const void* p : {(const void*)a.tokens, (const void*)a.positions, (const void*)a.tokens_out, a.paging ? (const void*)a.paging->table : nullptr})
     if ((uintptr_t)p % 4 != 0) return FLEET_EINVAL;
-  DevGraph* dg = nullptr;
-  int rc = get_graph(f, batch, &dg, n_tokens > 0);
-  if (rc) return rc;
+  DevGraph* dg = pick_graph(f, a.batch, a.n_tokens > 0);
+  if (!dg) return FLEET_EINVAL;
   const Graph& g = dg->g;
-  const int L = f->shape.n_layers, n_marks = L + 3, nx = f->info.n_xcd;
+  Work w;
+    work_layout(f, dg, f->work, &w);
+  const int L = f->shape.n_layers, nm = n_marks(L), nx = f->info.n_xcd;
   dev::Params P;
   memset(&P, 0, sizeof(P));
   fill_graph_params(P, dg);
-  P.buf[BUF_X] = f->x; P.buf[BUF_N] = f->n; P.buf[BUF_QKV] = f->qkv; P.buf[BUF_ATT] = f->att; P.buf[BUF_H] = f->h;
-  P.buf[BUF_PART] = f->part; P.buf[BUF_GPART] = f->gpart; P.buf[BUF_GU32] = f->gu32; P.buf[BUF_HIDDEN_IN] = (void*)hidden_in; P.buf[BUF_TOKENS] = (void*)tokens;
-  P.buf[BUF_KC] = k_cache; P.buf[BUF_VC] = v_cache; P.buf[BUF_POS] = (void*)positions;
-  P.buf[BUF_HIDDEN_OUT] = hidden_out; P.buf[BUF_LOGITS] = logits; P.buf[BUF_TOKENS_OUT] = tokens_out;
-  P.n_iter = n_tokens > 0 ? n_tokens : 1;
-  P.gpart_xcd_bytes = f->shape.sched_mode == FLEET_SCHED_UNAWARE ? 0 : (int32_t)f->gpart_bytes;
-  if (paging) {
-    P.buf[BUF_PT] = (void*)paging->table;
-    P.page_size = paging->page_size; P.n_pages = paging->n_pages; P.pt_stride = paging->stride;
+  P.ctr = w.ctr; P.status = w.status;
+  P.buf[BUF_X] = w.x; P.buf[BUF_N] = w.n; P.buf[BUF_QKV] = w.qkv; P.buf[BUF_ATT] = w.att; P.buf[BUF_H] = w.h;
+  P.buf[BUF_PART] = w.part; P.buf[BUF_GPART] = w.gpart; P.buf[BUF_GU32] = w.gu32;
+  P.buf[BUF_HIDDEN_IN] = (void*)a.hidden_in; P.buf[BUF_TOKENS] = (void*)a.tokens;
+  P.buf[BUF_KC] = a.k_cache; P.buf[BUF_VC] = a.v_cache; P.buf[BUF_POS] = (void*)a.positions;
+  P.buf[BUF_HIDDEN_OUT] = a.hidden_out; P.buf[BUF_LOGITS] = a.logits; P.buf[BUF_TOKENS_OUT] = a.tokens_out;
+  P.n_iter = a.n_tokens > 0 ? a.n_tokens : 1;
+  P.gpart_xcd_bytes = f->shape.sched_mode == FLEET_SCHED_UNAWARE ? 0 : (int32_t)w.gpart_region;
+  if (a.paging) {
+    P.buf[BUF_PT] = (void*)a.paging->table;
+    P.page_size = a.paging->page_size; P.n_pages = a.paging->n_pages; P.pt_stride = a.paging->stride;
   }
-  P.status = f->status; P.trace_cap = TRACE_CAP;
+  P.trace_cap = TRACE_CAP;
   // (no trace of a multi-step launch: the record area holds one step)
-  P.trace = (n_tokens == 0 && (f->shape.flags & (FLEET_FLAG_TRACE | FLEET_FLAG_TIMING))) ? f->trace : nullptr;
+  P.trace = (a.n_tokens == 0 && (f->shape.flags & (FLEET_FLAG_TRACE | FLEET_FLAG_TIMING))) ? f->trace : nullptr;
   P.rope = f->rope; P.timeout_ticks = f->timeout_ticks; P.n_xcd = nx; P.flags = f->shape.flags;
   P.nq = f->shape.n_q_heads; P.nkv = f->shape.n_kv_heads; P.hd = f->shape.head_dim; P.max_batch = f->shape.max_batch;
-  P.max_seq = f->shape.max_seq; P.hidden = f->shape.hidden; P.ffn = f->shape.ffn; P.batch = batch; P.eps = f->shape.rms_eps; P.vocab = f->shape.vocab;
-  const int mb = with_ingest ? 0 : 1 + layer_begin;
-  int me = with_final ? L + 2 : 1 + layer_end;
+  P.max_seq = f->shape.max_seq; P.hidden = f->shape.hidden; P.ffn = f->shape.ffn; P.batch = a.batch; P.eps = f->shape.rms_eps; P.vocab = f->shape.vocab;
+  // marks of a queue: ingest, layer 0 .. L-1, final stage, LM head, end.  The final stage
+  // (hidden_out, final norm) runs whenever asked for; the LM head only with a logits buffer.
+  const int mb = a.with_ingest ? 0 : 1 + a.layer_begin;
+  const int me = !a.with_final ? 1 + a.layer_end : (a.logits ? L + 3 : L + 2);
   for (int x = 0; x < nx; ++x) {
-    P.q_begin[x] = g.marks[(size_t)x * n_marks + mb];
-    P.q_end[x] = g.marks[(size_t)x * n_marks + me];
+    P.q_begin[x] = g.marks[(size_t)x * nm + mb];
+    P.q_end[x] = g.marks[(size_t)x * nm + me];
   }
-  // without the final stage and LM head the queue must stop before them; without
-  // logits the LM head is skipped by ending at the mark of the final stage + its
-  // own entries -- the final stage always runs when requested (it writes hidden_out)
-  int preset = with_ingest ? -1 : g.xready[layer_begin];
-  f->last_graph = dg;
+  if (a.x_in) HIP_TRY(hipMemcpyAsync(w.x, a.x_in, (size_t)a.batch * f->shape.hidden * 4, hipMemcpyDeviceToDevice, st));
+  const int preset = a.with_ingest ? -1 : g.xready[a.layer_begin];
+  f->last_status = w.status;
+  f->last_x = w.x;
   return launch(P, dg, f->info.n_cu, preset, st);
+}
+
+int check_step_args(const fleet* f, int batch, const void* hidden_in, const int32_t* tokens, const void* kc, const void* vc,
+                    const int32_t* positions, const float* hidden_out) {
+  if (!f || batch < 1 || batch > f->shape.max_batch || !kc || !vc || !positions || !hidden_out) return FLEET_EINVAL;
+  if (!hidden_in && !(tokens && f->embed)) return FLEET_EINVAL;
+  return FLEET_OK;
 }
 
 }  // namespace
@@ -408,9 +500,11 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
     if (!w->ln1[l] || !w->wqkv[l] || !w->q_norm[l] || !w->k_norm[l] || !w->wo[l] || !w->ln2[l] || !w->wgu[l] || !w->wdown[l])
       return FLEET_EINVAL;
   if (shape->vocab > 0 && (!w->final_norm || !w->lm_head)) return FLEET_EINVAL;
-  std::unique_ptr<fleet> f(new (std::nothrow) fleet());
+  std::unique_ptr<fleet> f(new (std::nothrow) fleet());   // its destructor frees what the steps below allocated
   if (!f) return FLEET_ENOMEM;
   f->shape = *shape;
+  // the FMA / MFMA switch is latched here: the packed copies and every graph follow it
+  f->fma_max = (shape->flags & FLEET_FLAG_PACKED_ONLY) ? 0 : fma_max_from_env();
   f->ln1.assign(w->ln1, w->ln1 + L); f->wqkv.assign(w->wqkv, w->wqkv + L); f->q_norm.assign(w->q_norm, w->q_norm + L);
   f->k_norm.assign(w->k_norm, w->k_norm + L); f->wo.assign(w->wo, w->wo + L); f->ln2.assign(w->ln2, w->ln2 + L);
   f->wgu.assign(w->wgu, w->wgu + L); f->wdown.assign(w->wdown, w->wdown + L);
@@ -420,22 +514,10 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
   for (int x = 0; x < f->info.n_xcd; ++x)
     if (f->info.per_xcd[x] == 0) return FLEET_EDEVICE;
 
-  const size_t mb = shape->max_batch, H = shape->hidden, F = shape->ffn;
+  const size_t H = shape->hidden, F = shape->ffn;
   const size_t NQKV = (size_t)(shape->n_q_heads + 2 * shape->n_kv_heads) * shape->head_dim;
   const size_t QD = (size_t)shape->n_q_heads * shape->head_dim;
-  const size_t grp = shape->n_q_heads / shape->n_kv_heads;
-  if ((rc = upload(&f->x, nullptr, mb * H * 4))) return rc;
-  // bf16 activations: feature dimension padded to whole 256-wide chunks (the MFMA kernels
-  // store them chunk-tiled)
-  // (the MFMA kernels store them as operand blocks of 16 rows)
-  auto pad256 = [](size_t k) { return (k + 255) / 256 * 256; };
-  const size_t mb16 = (mb + 15) / 16 * 16;
-  if ((rc = upload((char**)&f->n, nullptr, mb16 * pad256(H) * 2))) return rc;
-  if ((rc = upload(&f->qkv, nullptr, mb * NQKV * 4))) return rc;
-  if ((rc = upload((char**)&f->att, nullptr, mb16 * pad256(QD) * 2))) return rc;
-  if ((rc = upload((char**)&f->h, nullptr, mb16 * pad256(F) * 2))) return rc;
-  if ((rc = upload(&f->part, nullptr, mb * shape->n_kv_heads * 32 * grp * dev::PART_STRIDE * 4))) return rc;
-  if (shape->max_batch > fma_max_batch()) {
+  if (shape->max_batch > f->fma_max) {
     f->pk_qkv.assign(L, nullptr); f->pk_o.assign(L, nullptr); f->pk_gu.assign(L, nullptr); f->pk_down.assign(L, nullptr);
     for (int l = 0; l < L; ++l) {
       if ((rc = pack_matrix(&f->pk_qkv[l], f->wqkv[l], (int)NQKV, (int)H, true))) return rc;
@@ -446,19 +528,34 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
     if (shape->vocab > 0 && (rc = pack_matrix(&f->pk_lm, f->lm_head, shape->vocab, (int)H, true))) return rc;
     HIP_TRY(hipDeviceSynchronize());
   }
-  // partial sums of split-K GEMM tiles (MFMA kernels): up to 8 k-slices of the widest output a
-  // split plan can have, batch rows padded to the 64 one m-tile can hold
-  if (shape->max_batch > fma_max_batch()) {
-    size_t nmax = std::max({NQKV, H, 2 * F});
-    if (shape->vocab > 0 && (size_t)shape->vocab / 16 * 4 <= (size_t)GEMM_TILE_COUNTERS) nmax = std::max(nmax, (size_t)shape->vocab);
-    // (a region per XCD under the XCD-aware schedules)
-    f->gpart_bytes = 8 * 64 * nmax * 4;
-    if ((rc = upload(&f->gpart, nullptr, f->gpart_bytes * (shape->sched_mode == FLEET_SCHED_UNAWARE ? 1 : dev::MAX_XCD)))) return rc;
+  if (shape->flags & FLEET_FLAG_PACKED_ONLY) {   // the caller may free the matrices now: forget them
+    for (auto* v : {&f->wqkv, &f->wo, &f->wgu, &f->wdown}) v->assign(L, nullptr);
+    f->lm_head = nullptr;
   }
-  if (shape->flags & FLEET_FLAG_UNFUSED_SILU)   // fp32 [gate | up] sums of the unfused gate|up GEMM
-    if ((rc = upload(&f->gu32, nullptr, mb * 2 * F * 4))) return rc;
-  if ((rc = upload(&f->status, nullptr, dev::ST_WORDS * 4))) return rc;
-  HIP_TRY(hipMemset(f->status, 0, dev::ST_WORDS * 4));
+  // Batch buckets: powers of two, the last FMA batch, max_batch.  Every graph is built and
+  // uploaded here, so that a step allocates and copies nothing.
+  for (int b = 1; b < shape->max_batch; b *= 2) f->buckets.push_back(b);
+  if (f->fma_max >= 1 && f->fma_max < shape->max_batch) f->buckets.push_back(f->fma_max);
+  f->buckets.push_back(shape->max_batch);
+  std::sort(f->buckets.begin(), f->buckets.end());
+  f->buckets.erase(std::unique(f->buckets.begin(), f->buckets.end()), f->buckets.end());
+  const bool can_loop = shape->vocab > 0 && f->embed && f->final_norm;
+  for (int loop = 0; loop < (can_loop ? 2 : 1); ++loop)
+    for (int b : f->buckets) {
+      std::unique_ptr<DevGraph> dg(new (std::nothrow) DevGraph());
+      if (!dg) return FLEET_ENOMEM;
+      dg->g = build_decode_graph(f->shape, b, f->info.n_xcd, f->info.n_cu, loop != 0, f->fma_max);
+      if ((rc = upload_graph(dg.get(), f.get(), nullptr, f->info.n_xcd))) return rc;
+      f->work_bytes = std::max(f->work_bytes, work_layout(f.get(), dg.get(), nullptr, nullptr));
+      (loop ? f->graphs_loop : f->graphs).push_back(std::move(dg));
+    }
+  if ((rc = upload(&f->work, nullptr, f->work_bytes))) return rc;
+  {   // a status block that reads "ok" before the first step
+    Work w0;
+    work_layout(f.get(), f->graphs[0].get(), f->work, &w0);
+    HIP_TRY(hipMemset(w0.status, 0, dev::ST_WORDS * 4));
+    f->last_status = w0.status; f->last_x = w0.x;
+  }
   if (shape->flags & (FLEET_FLAG_TRACE | FLEET_FLAG_TIMING))
     if ((rc = upload(&f->trace, nullptr, ((size_t)f->info.n_cu * TRACE_CAP * 8 + f->info.n_cu) * 4))) return rc;
   // rotary table: angle = pos * theta^(-2i/d), evaluated in double
@@ -481,26 +578,21 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
 int fleet_destroy(fleet_t* f) {
   if (!f) return FLEET_OK;
   (void)hipDeviceSynchronize();
-  for (void* p : {(void*)f->x, f->n, (void*)f->qkv, f->att, f->h, (void*)f->part, (void*)f->gpart, (void*)f->gu32, (void*)f->rope, (void*)f->status, (void*)f->trace})
-    if (p) (void)hipFree(p);
-  for (auto* v : {&f->pk_qkv, &f->pk_o, &f->pk_gu, &f->pk_down})
-    for (void* p : *v) if (p) (void)hipFree(p);
-  if (f->pk_lm) (void)hipFree(f->pk_lm);
   delete f;
   return FLEET_OK;
 }
 
 int fleet_decode_step(fleet_t* f, int32_t batch, const void* hidden_in, const int32_t* tokens, void* k_cache,
                       void* v_cache, const int32_t* positions, float* hidden_out, float* logits, void* stream) {
-  if (!f || batch < 1 || batch > f->shape.max_batch || !k_cache || !v_cache || !positions || !hidden_out) return FLEET_EINVAL;
-  if (!hidden_in && !(tokens && f->embed)) return FLEET_EINVAL;
-  if (!logits && f->shape.vocab > 0) {
-    // the LM head is part of the step; callers that do not want logits run layers only
-    return FLEET_EINVAL;
-  }
-  return run_layers(f, batch, 0, f->shape.n_layers, true, true, hidden_in, tokens, k_cache, v_cache, positions,
-                    hidden_out, logits, (hipStream_t)stream);
+  int rc = check_step_args(f, batch, hidden_in, tokens, k_cache, v_cache, positions, hidden_out);
+  if (rc) return rc;
+  StepArgs a;
+  a.batch = batch; a.layer_end = f->shape.n_layers; a.with_ingest = a.with_final = true;
+  a.hidden_in = hidden_in; a.tokens = tokens; a.k_cache = k_cache; a.v_cache = v_cache; a.positions = positions;
+  a.hidden_out = hidden_out; a.logits = f->shape.vocab > 0 ? logits : nullptr;
+  return run_layers(f, a, (hipStream_t)stream);
 }
+
 
 int fleet_decode_layers(fleet_t* f, int32_t batch, int32_t layer_begin, int32_t layer_end, const float* x_in,
                         void* k_cache, void* v_cache, const int32_t* positions, float* x_out, float* logits,
@@ -509,13 +601,13 @@ int fleet_decode_layers(fleet_t* f, int32_t batch, int32_t layer_begin, int32_t 
   const int L = f->shape.n_layers;
   if (layer_begin < 0 || layer_end > L || layer_begin >= layer_end) return FLEET_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  const size_t bytes = (size_t)batch * f->shape.hidden * 4;
-  HIP_TRY(hipMemcpyAsync(f->x, x_in, bytes, hipMemcpyDeviceToDevice, st));
-  const bool fin = layer_end == L && logits && f->shape.vocab > 0;
-  int rc = run_layers(f, batch, layer_begin, layer_end, false, fin, nullptr, nullptr, k_cache, v_cache, positions,
-                      x_out, logits, st);
+  StepArgs a;
+  a.batch = batch; a.layer_begin = layer_begin; a.layer_end = layer_end;
+  a.with_final = layer_end == L && logits && f->shape.vocab > 0;
+  a.k_cache = k_cache; a.v_cache = v_cache; a.positions = positions; a.hidden_out = x_out; a.logits = logits; a.x_in = x_in;
+  int rc = run_layers(f, a, st);
   if (rc) return rc;
-  if (!fin) HIP_TRY(hipMemcpyAsync(x_out, f->x, bytes, hipMemcpyDeviceToDevice, st));
+  if (!a.with_final) HIP_TRY(hipMemcpyAsync(x_out, f->last_x, (size_t)batch * f->shape.hidden * 4, hipMemcpyDeviceToDevice, st));
   return FLEET_OK;
 }
 
@@ -523,17 +615,19 @@ int fleet_decode_step_paged(fleet_t* f, int32_t batch, const void* hidden_in, co
                             void* v_pool, const int32_t* page_table, int32_t page_size, int32_t n_pages,
                             int32_t table_stride, const int32_t* positions, float* hidden_out, float* logits,
                             void* stream) {
-  if (!f || batch < 1 || batch > f->shape.max_batch || !k_pool || !v_pool || !positions || !hidden_out || !page_table)
-    return FLEET_EINVAL;
-  if (!hidden_in && !(tokens && f->embed)) return FLEET_EINVAL;
-  if (!logits && f->shape.vocab > 0) return FLEET_EINVAL;   // the LM head is part of the step
+  int rc = check_step_args(f, batch, hidden_in, tokens, k_pool, v_pool, positions, hidden_out);
+  if (rc) return rc;
+  if (!page_table) return FLEET_EINVAL;
   if (page_size < 64 || (page_size & (page_size - 1)) || n_pages < 1 || table_stride < 1) return FLEET_EINVAL;
   // the kernel addresses a page with 32-bit page arithmetic inside one layer's pool
   if ((int64_t)n_pages * f->shape.n_kv_heads * page_size > (int64_t)1 << 40) return FLEET_EINVAL;
   KvPaging pg;
   pg.table = page_table; pg.page_size = page_size; pg.n_pages = n_pages; pg.stride = table_stride;
-  return run_layers(f, batch, 0, f->shape.n_layers, true, true, hidden_in, tokens, k_pool, v_pool, positions, hidden_out,
-                    logits, (hipStream_t)stream, 0, nullptr, &pg);
+  StepArgs a;
+  a.batch = batch; a.layer_end = f->shape.n_layers; a.with_ingest = a.with_final = true;
+  a.hidden_in = hidden_in; a.tokens = tokens; a.k_cache = k_pool; a.v_cache = v_pool; a.positions = positions;
+  a.hidden_out = hidden_out; a.logits = f->shape.vocab > 0 ? logits : nullptr; a.paging = &pg;
+  return run_layers(f, a, (hipStream_t)stream);
 }
 
 int fleet_decode_tokens(fleet_t* f, int32_t batch, int32_t* tokens, void* k_cache, void* v_cache, int32_t* positions,
@@ -541,9 +635,12 @@ int fleet_decode_tokens(fleet_t* f, int32_t batch, int32_t* tokens, void* k_cach
   if (!f || batch < 1 || batch > f->shape.max_batch || !tokens || !k_cache || !v_cache || !positions || !tokens_out ||
       !hidden_out || !logits || n_tokens < 1 || n_tokens > 65536)
     return FLEET_EINVAL;
-  if (f->shape.vocab <= 0 || !f->embed || !f->lm_head || !f->final_norm) return FLEET_EINVAL;
-  return run_layers(f, batch, 0, f->shape.n_layers, true, true, nullptr, tokens, k_cache, v_cache, positions, hidden_out,
-                    logits, (hipStream_t)stream, n_tokens, tokens_out);
+  if (f->shape.vocab <= 0 || !f->embed || !f->final_norm || f->graphs_loop.empty()) return FLEET_EINVAL;
+  StepArgs a;
+  a.batch = batch; a.layer_end = f->shape.n_layers; a.with_ingest = a.with_final = true;
+  a.tokens = tokens; a.k_cache = k_cache; a.v_cache = v_cache; a.positions = positions;
+  a.hidden_out = hidden_out; a.logits = logits; a.n_tokens = n_tokens; a.tokens_out = tokens_out;
+  return run_layers(f, a, (hipStream_t)stream);
 }
 
 int fleet_last_status(fleet_t* f, fleet_status_t* out) {
@@ -552,7 +649,7 @@ int fleet_last_status(fleet_t* f, fleet_status_t* out) {
   hipError_t e = hipDeviceSynchronize();
   out->hip_error = e != hipSuccess ? (int)e : g_last_hip;
   int32_t st[dev::ST_WORDS];
-  HIP_TRY(hipMemcpy(st, f->status, sizeof(st), hipMemcpyDeviceToHost));
+  HIP_TRY(hipMemcpy(st, f->last_status, sizeof(st), hipMemcpyDeviceToHost));
   out->code = e != hipSuccess ? FLEET_EHIP : st[dev::ST_CODE];
   out->task = st[dev::ST_TASK]; out->event = st[dev::ST_EVENT];
   out->observed = st[dev::ST_OBSERVED]; out->needed = st[dev::ST_NEEDED];
@@ -561,12 +658,7 @@ int fleet_last_status(fleet_t* f, fleet_status_t* out) {
   return FLEET_OK;
 }
 
-int fleet_graph_build(const fleet_shape_t* shape, int32_t batch, int32_t n_xcd, int32_t n_workers, void* buf, size_t* len) {
-  if (!shape || !len || batch < 1 || n_xcd < 1 || n_xcd > dev::MAX_XCD || n_workers < n_xcd) return FLEET_EINVAL;
-  int rc = check_shape(*shape);
-  if (rc) return rc;
-  if (batch > shape->max_batch) return FLEET_EINVAL;
-  std::vector<int32_t> words = build_decode_graph(*shape, batch, n_xcd, n_workers).serialize();
+static int copy_words(const std::vector<int32_t>& words, void* buf, size_t* len) {
   const size_t need = words.size() * 4;
   if (!buf || *len < need) { *len = need; return buf ? FLEET_ESMALL : FLEET_OK; }
   memcpy(buf, words.data(), need);
@@ -574,17 +666,20 @@ int fleet_graph_build(const fleet_shape_t* shape, int32_t batch, int32_t n_xcd, 
   return FLEET_OK;
 }
 
+int fleet_graph_build(const fleet_shape_t* shape, int32_t batch, int32_t n_xcd, int32_t n_workers, void* buf, size_t* len) {
+  if (!shape || !len || batch < 1 || n_xcd < 1 || n_xcd > dev::MAX_XCD || n_workers < n_xcd) return FLEET_EINVAL;
+  int rc = check_shape(*shape);
+  if (rc) return rc;
+  if (batch > shape->max_batch) return FLEET_EINVAL;
+  const int fma_max = (shape->flags & FLEET_FLAG_PACKED_ONLY) ? 0 : fma_max_from_env();
+  return copy_words(build_decode_graph(*shape, batch, n_xcd, n_workers, false, fma_max).serialize(), buf, len);
+}
+
 int fleet_graph_dump(fleet_t* f, int32_t batch, void* buf, size_t* len) {
   if (!f || !len || batch < 1 || batch > f->shape.max_batch) return FLEET_EINVAL;
-  DevGraph* dg = nullptr;
-  int rc = get_graph(f, batch, &dg);
-  if (rc) return rc;
-  std::vector<int32_t> words = dg->g.serialize();
-  const size_t need = words.size() * 4;
-  if (!buf || *len < need) { *len = need; return buf ? FLEET_ESMALL : FLEET_OK; }
-  memcpy(buf, words.data(), need);
-  *len = need;
-  return FLEET_OK;
+  DevGraph* dg = pick_graph(f, batch, false);
+  if (!dg) return FLEET_EINVAL;
+  return copy_words(dg->g.serialize(), buf, len);
 }
 
 int fleet_trace_read(fleet_t* f, void* buf, size_t* len) {
@@ -606,17 +701,14 @@ int fleet_trace_read(fleet_t* f, void* buf, size_t* len) {
     out[i + 3] -= t0; out[i + 6] -= t0; out[i + 7] -= t0;
     if (timing) { out[i + 4] -= t0; out[i + 5] -= t0; }
   }
-  const size_t need = out.size() * 4;
-  if (!buf || *len < need) { *len = need; return buf ? FLEET_ESMALL : FLEET_OK; }
-  memcpy(buf, out.data(), need);
-  *len = need;
-  return FLEET_OK;
+  return copy_words(out, buf, len);
 }
 
 int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const* w_copies, int32_t n_copies, float* y,
                int32_t sched_mode, int32_t tile_m, int32_t flags, int32_t reps, void* stream, float* elapsed_ms) {
-  if (B < 1 || B > 64 || K < 32 || K % 32 || N < 16 || N % 16 || !x || !w_copies || n_copies < 1 || !y || reps < 1 || reps > 4096)
+  if (B < 1 || B > MAX_BATCH || K < 32 || K % 32 || N < 16 || N % 16 || !x || !w_copies || n_copies < 1 || !y || reps < 1 || reps > 4096)
     return FLEET_EINVAL;
+  if ((int64_t)N * K * 2 >= (int64_t)1 << 31) return FLEET_EINVAL;   // 32-bit byte offsets inside a matrix
   if (sched_mode < FLEET_SCHED_COOPERATIVE || sched_mode > FLEET_SCHED_MSPLIT) return FLEET_EINVAL;
   if (tile_m != 0 && tile_m != 16 && tile_m != 32 && tile_m != 64) return FLEET_EINVAL;
   for (int i = 0; i < n_copies; ++i) if (!w_copies[i]) return FLEET_EINVAL;
@@ -624,41 +716,50 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const
   int rc = probe_device(&info, nullptr, 0);
   if (rc) return rc;
   DevGraph dg;
-  dg.g = build_gemm_graph(B, K, N, sched_mode, tile_m, flags, reps, n_copies, info.n_xcd, info.n_cu);
+  dg.g = build_gemm_graph(B, K, N, sched_mode, tile_m, flags, reps, n_copies, info.n_xcd, info.n_cu, fma_max_from_env());
   // the MFMA kernels read operand blocks: pack the caller's matrices into private copies
   const bool mfma = dg.g.header[H_PATH] == P_MFMA;
   std::vector<void*> packed;
   void* xp = nullptr;
-  auto free_packed = [&]() { for (void* p : packed) if (p) (void)hipFree(p); if (xp) (void)hipFree(xp); };
+  int32_t* status = nullptr;
+  uint32_t* ctr = nullptr;
+  float* gpart = nullptr;   // partial sums of split-K tiles
+  auto free_all = [&]() {
+    for (void* p : packed) if (p) (void)hipFree(p);
+    for (void* p : {(void*)xp, (void*)status, (void*)ctr, (void*)gpart}) if (p) (void)hipFree(p);
+  };
   if (mfma) {
     packed.assign(n_copies, nullptr);
     for (int i = 0; i < n_copies; ++i)
-      if ((rc = pack_matrix(&packed[i], w_copies[i], N, K, true))) { free_packed(); return rc; }
-    if ((rc = pack_matrix(&xp, x, B, K, false))) { free_packed(); return rc; }
-    if (hipDeviceSynchronize() != hipSuccess) { free_packed(); return FLEET_EHIP; }
+      if ((rc = pack_matrix(&packed[i], w_copies[i], N, K, true))) { free_all(); return rc; }
+    if ((rc = pack_matrix(&xp, x, B, K, false))) { free_all(); return rc; }
+    if (hipDeviceSynchronize() != hipSuccess) { free_all(); return FLEET_EHIP; }
   }
-  if ((rc = upload_graph(&dg, nullptr, mfma ? (const void* const*)packed.data() : w_copies, info.n_xcd))) { free_packed(); return rc; }
-  int32_t* status = nullptr;
-  if ((rc = upload(&status, nullptr, dev::ST_WORDS * 4))) { free_packed(); return rc; }
-  float* gpart = nullptr;   // partial sums of split-K tiles
-  const size_t gpart_bytes = (size_t)8 * 64 * N * 4;   // one region; one per XCD under the XCD-aware schedules
-  if ((rc = upload(&gpart, nullptr, gpart_bytes * (sched_mode == FLEET_SCHED_UNAWARE ? 1 : dev::MAX_XCD)))) { (void)hipFree(status); free_packed(); return rc; }
+  if ((rc = upload_graph(&dg, nullptr, mfma ? (const void* const*)packed.data() : w_copies, info.n_xcd))) { free_all(); return rc; }
+  if ((rc = upload(&status, nullptr, dev::ST_WORDS * 4))) { free_all(); return rc; }
+  if ((rc = upload(&ctr, nullptr, (size_t)dg.ctr_words * 4))) { free_all(); return rc; }
+  // one region of partial sums: 8 k-slices of the batch padded to whole tiles; one region
+  // per XCD under the XCD-aware schedules
+  const size_t gpart_bytes = (size_t)8 * ((B + MAX_TILE_ROWS - 1) / MAX_TILE_ROWS * MAX_TILE_ROWS) * N * 4;
+  if ((rc = upload(&gpart, nullptr, gpart_bytes * (sched_mode == FLEET_SCHED_UNAWARE ? 1 : dev::MAX_XCD)))) { free_all(); return rc; }
   dev::Params P;
   memset(&P, 0, sizeof(P));
   fill_graph_params(P, &dg);
+  P.ctr = ctr;
   P.buf[BUF_GEMM_X] = mfma ? xp : (void*)x; P.buf[BUF_GEMM_Y] = y; P.buf[BUF_GPART] = gpart;
   P.gpart_xcd_bytes = sched_mode == FLEET_SCHED_UNAWARE ? 0 : (int32_t)gpart_bytes;
   P.n_iter = 1;
   P.status = status; P.timeout_ticks = timeout_ticks_from_env(); P.n_xcd = info.n_xcd; P.flags = flags;
   P.batch = B; P.hidden = K;
-  for (int xc = 0; xc < info.n_xcd; ++xc) { P.q_begin[xc] = dg.g.marks[(size_t)xc * 3 + 0]; P.q_end[xc] = dg.g.marks[(size_t)xc * 3 + 2]; }
+  const int nm = n_marks(0);
+  for (int xc = 0; xc < info.n_xcd; ++xc) { P.q_begin[xc] = dg.g.marks[(size_t)xc * nm + 0]; P.q_end[xc] = dg.g.marks[(size_t)xc * nm + nm - 1]; }
   hipStream_t st = (hipStream_t)stream;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   hipError_t he = hipEventCreate(&e0);
   if (he == hipSuccess) he = hipEventCreate(&e1);
   if (he == hipSuccess) {
     const int words = dg.ctr_words;
-    hipLaunchKernelGGL(fleet_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, st, dg.ctr, words, -1, 0u, status, 0, 1, 0, -1);
+    hipLaunchKernelGGL(fleet_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, st, ctr, words, -1, 0u, status, 0, 1, 0, -1);
     (void)hipEventRecord(e0, st);
     int lrc = launch_persistent(&dg, P, info.n_cu, st);
     (void)hipEventRecord(e1, st);
@@ -670,9 +771,7 @@ int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const
   if (he == hipSuccess) he = hipMemcpy(code, status, sizeof(code), hipMemcpyDeviceToHost);
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
-  (void)hipFree(status);
-  (void)hipFree(gpart);
-  free_packed();
+  free_all();
   if (he != hipSuccess) { g_last_hip = (int)he; return FLEET_EHIP; }
   return code[dev::ST_CODE];
 }
@@ -684,18 +783,26 @@ int fleet_copy(void* dst, const void* src, size_t bytes, void* stream) {
   return FLEET_OK;
 }
 
+// Closed forms: a non-positive divisor is a caller error and gives -1 (0.0 for the model).
 int64_t fleet_weight_bytes(int32_t K, int32_t N) { return (int64_t)K * N * 2; }
-int64_t fleet_weight_bytes_per_xcd(int32_t K, int32_t N, int32_t n_xcd) { return (int64_t)K * N * 2 / n_xcd; }
+int64_t fleet_weight_bytes_per_xcd(int32_t K, int32_t N, int32_t n_xcd) {
+  return n_xcd > 0 ? (int64_t)K * N * 2 / n_xcd : -1;
+}
 int64_t fleet_l2_window_bytes(int32_t N, int32_t n_xcd, int32_t tile_n, int32_t tile_k) {
   // one K-chunk of every N-tile of a chiplet's partition (Table "weight sizes")
+  if (n_xcd <= 0 || tile_n <= 0) return -1;
   return (int64_t)(N / n_xcd / tile_n) * tile_n * tile_k * 2;
 }
 double fleet_l2_hit_model(int32_t batch, int32_t tile_m, int32_t workers_per_xcd) {
+  if (batch < 1 || tile_m < 0 || workers_per_xcd < 1) return 0.0;
+  if (tile_m == 0) tile_m = std::min(MAX_TILE_ROWS, (batch + 15) / 16 * 16);   // whole-batch tile, as in the shape
   const int m_tiles = (batch + tile_m - 1) / tile_m;
   const int R = std::min(workers_per_xcd, m_tiles);
   return R > 0 ? (double)(R - 1) / R : 0.0;
 }
-double fleet_effective_intensity(int32_t batch, double l2_hit) { return (double)batch / (1.0 - l2_hit); }
+double fleet_effective_intensity(int32_t batch, double l2_hit) {
+  return l2_hit < 1.0 ? (double)batch / (1.0 - l2_hit) : 0.0;
+}
 int64_t fleet_step_bytes(const fleet_shape_t* s, int32_t batch, const int32_t* positions) {
   if (!s || !positions) return -1;
   const int64_t H = s->hidden, F = s->ffn, hd = s->head_dim;

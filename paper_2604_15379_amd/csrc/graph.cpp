@@ -235,16 +235,15 @@ static MfmaPlan plan_for(int sched, int flags, int n_units, int K, int nb, int t
 // batch 3 on (per step: batch 2 3.77 ms with either, batch 3 4.41 ms FMA / 3.80 ms MFMA, batch 4
 // 4.58 / 3.78), so the default is 2; the environment variable FLEET_FMA_MAX_BATCH (0..8) moves
 // the switch, e.g. to 8 for FMA at batch 3-8.
-static int fma_max() {
+int fma_max_from_env() {
   const char* e = getenv("FLEET_FMA_MAX_BATCH");
   if (!e) return 2;
   return std::min(8, std::max(0, atoi(e)));
 }
-int fma_max_batch() { return fma_max(); }
 
-int resolve_tile_m(int batch, int tile_m) {
-  if (batch <= fma_max()) return batch;  // FMA GEMV path: one tile holds the whole batch
-  if (tile_m == 0) return ((batch + 15) / 16) * 16;
+int resolve_tile_m(int batch, int tile_m, int fma_max) {
+  if (batch <= fma_max) return batch;  // FMA GEMV path: one tile holds the whole batch
+  if (tile_m == 0) return std::min(MAX_TILE_ROWS, ((batch + 15) / 16) * 16);
   return tile_m;
 }
 
@@ -263,20 +262,29 @@ int check_shape(const fleet_shape_t& s) {
   if (s.n_q_heads % s.n_kv_heads || s.n_q_heads / s.n_kv_heads > 4) return FLEET_EINVAL;
   if (s.hidden % 32 || s.ffn % 32) return FLEET_EINVAL;
   if (s.vocab < 0 || s.vocab % 16) return FLEET_EINVAL;
-  if (s.max_batch < 1 || s.max_batch > 64 || s.max_seq < 1) return FLEET_EINVAL;
+  if (s.max_batch < 1 || s.max_batch > MAX_BATCH || s.max_seq < 1) return FLEET_EINVAL;
+  // the kernels address one weight matrix, and one (sequence, kv head) stream of the cache,
+  // with 32-bit byte offsets
+  const int64_t lim = (int64_t)1 << 31;
+  const int64_t H = s.hidden, F = s.ffn, QD = (int64_t)s.n_q_heads * s.head_dim;
+  const int64_t NQKV = (int64_t)(s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim;
+  if (NQKV * H * 2 >= lim || QD * H * 2 >= lim || 2 * F * H * 2 >= lim || (int64_t)s.vocab * H * 2 >= lim) return FLEET_EINVAL;
+  if ((int64_t)s.max_seq * s.head_dim * 2 >= lim) return FLEET_EINVAL;
+  // one arrival counter per (sequence, kv head) for the split-KV merge
+  if ((int64_t)s.max_batch * s.n_kv_heads > MAX_BATCH * 8) return FLEET_EINVAL;
   if (s.sched_mode < FLEET_SCHED_COOPERATIVE || s.sched_mode > FLEET_SCHED_MSPLIT) return FLEET_EINVAL;
   if (s.tile_m != 0 && s.tile_m != 16 && s.tile_m != 32 && s.tile_m != 64) return FLEET_EINVAL;
   if (!(s.rms_eps >= 0.f) || !(s.rope_theta > 0.f)) return FLEET_EINVAL;
   return FLEET_OK;
 }
 
-Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_workers, bool loop) {
+Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_workers, bool loop, int fma_max) {
   Builder b(n_xcd, n_workers, s.sched_mode, batch);
   const int H = s.hidden, hd = s.head_dim, nq = s.n_q_heads, nkv = s.n_kv_heads, F = s.ffn;
   const int QD = nq * hd, NQKV = (nq + 2 * nkv) * hd;
-  const Path path = batch <= fma_max() ? P_FMA : P_MFMA;
+  const Path path = batch <= fma_max ? P_FMA : P_MFMA;
   const int ur = path == P_FMA ? 8 : 16;
-  const int tm = resolve_tile_m(batch, s.tile_m);
+  const int tm = resolve_tile_m(batch, s.tile_m, fma_max);
   const int mt = (batch + tm - 1) / tm;
   const int S = attention_splits(batch, nkv, n_workers, s.max_seq);
 
@@ -388,6 +396,7 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   int op_fin = b.add_op(B_FINAL, -1, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N,
                         s.vocab > 0 ? 1 : 0, W_FINAL);
   ev = b.cu_stage(op_fin, batch, ev, row_key, row_arg);
+  b.mark_all();   // a step without logits ends here
   if (s.vocab > 0) {
     int op_lm = b.add_op(B_GEMM, -1, E_STORE_F32, path, H, s.vocab, ur, s.vocab / ur, mt, tm, BUF_N,
                          BUF_LOGITS, 0, W_LM, (xmode(H) << 8) | PRE2 | plan_bits(s.vocab / ur, H, 1));
@@ -402,11 +411,11 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
 }
 
 Graph build_gemm_graph(int B, int K, int N, int sched_mode, int tile_m, int flags, int reps,
-                       int n_copies, int n_xcd, int n_workers) {
+                       int n_copies, int n_xcd, int n_workers, int fma_max) {
   Builder b(n_xcd, n_workers, sched_mode, B);
-  const Path path = B <= fma_max() ? P_FMA : P_MFMA;
+  const Path path = B <= fma_max ? P_FMA : P_MFMA;
   const int ur = path == P_FMA ? 8 : 16;
-  const int tm = resolve_tile_m(B, tile_m);
+  const int tm = resolve_tile_m(B, tile_m, fma_max);
   const int mt = (B + tm - 1) / tm;
   int ev = -1;
   b.mark_all();
@@ -427,6 +436,7 @@ Graph build_gemm_graph(int B, int K, int N, int sched_mode, int tile_m, int flag
     ev = b.gemm_stage(op, wait);
     evs.push_back(ev);
   }
+  b.mark_all();
   b.mark_all();
   b.g.xready.push_back(-1);
   return b.finish(0, tm, path, 1, mt);

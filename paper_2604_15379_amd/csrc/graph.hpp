@@ -14,8 +14,8 @@
 //   events [n_events][EVENT_WORDS]
 //   qoff   [n_xcd + 1]                  first queue entry of each XCD's queue
 //   qents  [n_qent  ][QENT_WORDS]       the per-XCD queues, concatenated
-//   marks  [n_xcd][n_layers + 3]        queue index (within the XCD's queue) of:
-//                                       ingest, layer 0..L-1, final stage, end
+//   marks  [n_xcd][n_layers + 4]        queue index (within the XCD's queue) of:
+//                                       ingest, layer 0..L-1, final stage, LM head, end
 //   xready [n_layers + 1]               event after which the residual stream
 //                                       entering layer l is complete
 #pragma once
@@ -107,10 +107,16 @@ struct MfmaPlan { int G, KS, resident; };
 MfmaPlan plan_mfma(int units_per_xcd, int workers_per_xcd, int K, int nb, int mt_blocks, int m_tiles, bool allow_split);
 // 16-row blocks of batch rows the MFMA kernel for tile height tile_m accumulates (1, 2 or 4)
 int mfma_blocks(int tile_m);
-// largest batch that runs the FMA GEMV kernels (larger batches run the MFMA kernels)
-int fma_max_batch();
-// tile_m actually used for `batch` (0 = whole batch rounded up to 16; FMA path: batch)
-int resolve_tile_m(int batch, int tile_m);
+// largest batch that runs the FMA GEMV kernels (larger batches run the MFMA kernels): 2, or
+// what the environment variable FLEET_FMA_MAX_BATCH (0..8) says.  Read once by whoever owns
+// a set of graphs (fleet_create, fleet_gemm, fleet_graph_build) and handed to the builders, so
+// that the graphs and the packed weight copies of one owner always agree.
+int fma_max_from_env();
+constexpr int MAX_TILE_ROWS = 64;   // batch rows one MFMA tile can hold (4 blocks of 16)
+constexpr int MAX_BATCH = 128;
+// tile_m actually used for `batch` (0 = whole batch rounded up to 16, at most MAX_TILE_ROWS;
+// FMA path: batch)
+int resolve_tile_m(int batch, int tile_m, int fma_max);
 // KV splits per (sequence, kv head)
 int attention_splits(int batch, int n_kv_heads, int n_workers, int max_seq);
 // validate a shape; returns FLEET_OK or FLEET_EINVAL
@@ -119,9 +125,11 @@ int check_shape(const fleet_shape_t& s);
 // the decode-step graph for `batch` sequences on n_xcd chiplets, n_workers workgroups
 // loop = true: a last stage of ARGMAX CU-tasks (greedy next token, one per sequence) so that a
 // launch can run several decode steps back to back
-Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_workers, bool loop = false);
+Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_workers, bool loop, int fma_max);
 // `reps` GEMM device-tasks y = x W^T (rep i reads weight copy i % n_copies)
 Graph build_gemm_graph(int B, int K, int N, int sched_mode, int tile_m, int flags, int reps,
-                       int n_copies, int n_xcd, int n_workers);
+                       int n_copies, int n_xcd, int n_workers, int fma_max);
+// marks per XCD of a decode graph with n_layers layers
+inline int n_marks(int n_layers) { return n_layers + 4; }
 
 }  // namespace fleetg

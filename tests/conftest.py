@@ -21,3 +21,14 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Report the measured share of new cache entries that matched the oracle bit for bit."""
+    try:
+        from gpu_common import KV_BIT_EQUAL
+    except Exception:
+        return
+    if KV_BIT_EQUAL:
+        terminalreporter.write_line(f"new layer-0 K/V entries bit-equal to the oracle: min {min(KV_BIT_EQUAL):.4f} "
+                                    f"mean {sum(KV_BIT_EQUAL) / len(KV_BIT_EQUAL):.4f} over {len(KV_BIT_EQUAL)} checks")

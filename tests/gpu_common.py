@@ -8,6 +8,10 @@ import paper_2604_15379_amd as F
 import synth_inputs as si
 
 TOL = 2e-2   # max |err| <= TOL * RMS(reference): the bar stated for hidden states and logits
+# Fraction of the new layer-0 cache entries that must equal the oracle's bit for bit (the others
+# sit one bf16 step away: the two sides add the same products in different orders).
+KV_BIT_EQUAL_MIN = 0.7
+KV_BIT_EQUAL = []   # fractions seen in this process (reported at the end of the run)
 
 
 def rms(a):
@@ -93,7 +97,9 @@ def check_new_kv(model: Model, k_gpu, v_gpu, k_ref, v_ref):
         r = si.bf16_bits_to_f32(ref).astype(np.float64)
         assert np.all(np.abs(g[first] - r[first]) <= np.abs(r[first]) * 2.0 ** -7 + 5e-3 * rms(r[first])), \
             f"new {nm} entries of layer 0 differ by more than one bf16 step"
-        assert np.mean(got[first] == ref[first]) > 0.7, f"too many new {nm} entries differ"
+        same = float(np.mean(got[first] == ref[first]))
+        KV_BIT_EQUAL.append(same)
+        assert same > KV_BIT_EQUAL_MIN, f"too many new {nm} entries differ: {same:.3f} bit-equal"
         err = np.abs(g[changed] - r[changed]).max()
         assert err <= TOL * rms(r[changed]) + 2.0 ** -7 * np.abs(r[changed]).max(), \
             f"new {nm} entries: max|err| {err:.3e}"

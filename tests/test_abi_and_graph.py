@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_graph_build_rejects_bad_shapes():
     sh = si.reduced_shape().asdict()
-    for bad in ({"head_dim": 64}, {"hidden": 1000}, {"n_q_heads": 7}, {"max_batch": 65},
+    for bad in ({"head_dim": 64}, {"hidden": 1000}, {"n_q_heads": 7}, {"max_batch": 129},
                 {"vocab": 1001}, {"n_layers": 0}):
         with pytest.raises(F.FleetError):
             F.fleet_graph_build({**sh, **bad}, 1)
@@ -37,6 +37,61 @@ def test_graph_build_rejects_bad_shapes():
         F.fleet_graph_build(sh, 2)           # batch above max_batch
     with pytest.raises(F.FleetError):
         F.fleet_graph_build(sh, 1, tile_m=24)
+
+
+def test_shapes_beyond_32bit_offsets_are_rejected():
+    """The kernels address a weight matrix and one (sequence, kv head) stream of the cache with
+    32-bit byte offsets: a matrix of 2 GiB or more, or max_seq * 256 >= 2^31, is refused."""
+    q = si.qwen3_8b_shape(1, 1025, n_layers=1).asdict()
+    F.fleet_graph_build(q, 1)                                     # the real shape passes
+    for bad in ({"vocab": 262144},                                # 262144 * 4096 * 2 = 2^31
+                {"ffn": 131072},                                  # gate|up: 2 * 131072 * 4096 * 2 = 2^31
+                {"max_seq": 1 << 23},                             # 2^23 * 256 = 2^31
+                {"max_batch": 128, "n_kv_heads": 16}):            # more (sequence, kv head) pairs than counters
+        with pytest.raises(F.FleetError):
+            F.fleet_graph_build({**q, **bad}, 1)
+    F.fleet_graph_build({**q, "vocab": 262144 - 16}, 1)
+    F.fleet_graph_build({**q, "max_batch": 128}, 128)
+
+
+def test_closed_forms_survive_zero_divisors():
+    """Nothing in the ABI ends the process: a zero divisor gives -1 (0.0 for the hit model), and
+    tile_m = 0 means the whole-batch tile as it does in the shape."""
+    assert F.fleet_weight_bytes_per_xcd(4096, 4096, 0) == -1
+    assert F.fleet_l2_window_bytes(4096, 0, 64, 256) == -1
+    assert F.fleet_l2_window_bytes(4096, 8, 0, 256) == -1
+    assert F.fleet_l2_hit_model(64, 16, 0) == 0.0
+    assert F.fleet_l2_hit_model(0, 16, 32) == 0.0
+    assert F.fleet_l2_hit_model(64, 0, 32) == 0.0                 # one 64-row tile: nothing to share
+    assert F.fleet_l2_hit_model(128, 0, 32) == pytest.approx(0.5)  # two 64-row tiles
+    assert F.fleet_effective_intensity(8, 1.0) == 0.0
+
+
+def test_fma_switch_follows_the_environment_of_the_builder(monkeypatch):
+    """FLEET_FMA_MAX_BATCH is read once per owner of a graph set (here: per fleet_graph_build
+    call) and handed to the builder; FLEET_FLAG_PACKED_ONLY forces the MFMA path for every batch."""
+    sh = si.reduced_shape(max_batch=8).asdict()
+    path = lambda b, flags=0: F.parse_graph(F.fleet_graph_build(sh, b, flags=flags))["header"]["path"]
+    assert [path(b) for b in (1, 2, 3, 8)] == [0, 0, 1, 1]
+    monkeypatch.setenv("FLEET_FMA_MAX_BATCH", "8")
+    assert [path(b) for b in (1, 2, 3, 8)] == [0, 0, 0, 0]
+    assert [path(b, F.FLAG_PACKED_ONLY) for b in (1, 8)] == [1, 1]
+    monkeypatch.setenv("FLEET_FMA_MAX_BATCH", "0")
+    assert [path(b) for b in (1, 2)] == [1, 1]
+
+
+def test_marks_let_a_step_end_before_the_lm_head():
+    """Per XCD the queue marks are: ingest, every layer, final stage, LM head, end; the slice
+    between the last two holds exactly the LM-head tasks (a step without logits stops there)."""
+    sh = si.reduced_shape(max_batch=4, n_layers=3, vocab=512)
+    g = F.parse_graph(F.fleet_graph_build(sh.asdict(), 4))
+    assert g["marks"].shape == (8, 3 + 4)
+    lm_op = [i for i, o in enumerate(g["ops"]) if o[13] == WK["LM"]][0]
+    for x in range(8):
+        q = g["qents"][g["qoff"][x]:g["qoff"][x + 1]]
+        tail = q[g["marks"][x, -2]:g["marks"][x, -1]]
+        assert len(tail) >= 1 and all(g["tasks"][e[0], 0] == lm_op for e in tail)
+        assert all(g["tasks"][e[0], 0] != lm_op for e in q[:g["marks"][x, -2]])
 
 
 # ------------------------------------------------------------------ paper tables
@@ -89,7 +144,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
     H, hd, nq, nkv, Fd = sh.hidden, sh.head_dim, sh.n_q_heads, sh.n_kv_heads, sh.ffn
     fma = batch <= FMA_MAX
     ur = 8 if fma else 16
-    tm = batch if fma else (tile_m or -(-batch // 16) * 16)
+    tm = batch if fma else (tile_m or min(64, -(-batch // 16) * 16))
     mt = -(-batch // tm)
     S = 1
     while S * 2 <= 32 and batch * nkv * S * 2 <= n_workers and S * 2 * 128 <= sh.max_seq:
@@ -264,6 +319,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
     mark()
     ev = cu_stage(op(FINAL, -1, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 1 if sh.vocab else 0, WK["FINAL"]),
                   rows, ev)
+    mark()      # a step without logits ends here
     if sh.vocab:
         gemm_stage(op(GEMM, -1, 0, path, H, sh.vocab, ur, sh.vocab // ur, mt, tm, BUF["N"], BUF["LOGITS"], 0,
                       WK["LM"], xm(H) | plan(sh.vocab // ur, H, 1)), ev)
@@ -279,6 +335,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
 CASES = [
     (si.reduced_shape(max_batch=64, n_layers=2, vocab=2064), [1, 2, 5, 8, 9, 33, 64], 8, 256),
     (si.qwen3_8b_shape(64, 4097, n_layers=3), [1, 2, 8, 32, 64], 8, 256),
+    (si.qwen3_8b_shape(128, 513, n_layers=1), [65, 100, 128], 8, 256),   # two 64-row m-tiles
     (si.reduced_shape(max_batch=4), [1, 3], 4, 120),          # another chiplet count / CU count
 ]
 

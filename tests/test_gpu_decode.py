@@ -133,23 +133,131 @@ def test_misaligned_buffers_are_rejected():
 
 
 def test_one_fleet_many_batch_sizes():
-    """One fleet_t serves steps of different batch sizes in any order (a graph per batch size,
-    built on first use and cached; shared scratch activations and counters): every step equals
-    the oracle, including repeats of a size seen before."""
+    """One fleet_t serves steps of any batch size up to max_batch in any order without building
+    anything on the way: fleet_create made one graph per batch bucket (powers of two and
+    max_batch), a step runs the smallest bucket that holds it and the tasks of the rows it does
+    not have only follow their events.  Every step equals the oracle, rows beyond the batch are
+    never written, and no step allocates device memory (the free memory of the device does not
+    move over all the steps; every tensor the steps use exists before)."""
     sh = si.reduced_shape(max_batch=40, max_seq=96, n_layers=2, vocab=1024)
     base = Model(sh, seed=70, batch=40, positions=np.random.default_rng(70).integers(0, 96, 40).astype(np.int32))
     f = F.fleet_create(sh.asdict(), base.w, 0, 0, 0)
     try:
-        for batch in (1, 5, 40, 2, 5, 17, 1):
-            print(f"  step with batch {batch}", flush=True)
+        sizes = (1, 5, 40, 2, 5, 17, 1, 3, 33)
+        assert [F.parse_graph(F.fleet_graph_dump(f, b))["header"]["batch"] for b in (1, 2, 3, 5, 17, 33, 40)] == \
+            [1, 2, 4, 8, 32, 40, 40]
+        models = {}
+        for batch in set(sizes):
             pos = np.random.default_rng(100 + batch).integers(0, 96, batch).astype(np.int32)
-            m = Model(sh, seed=70, batch=batch, positions=pos)   # same seed: same weights as the fleet's
-            (ho, lg), k, v = m.run_oracle()
-            got = m.run_gpu(fleet=f)
+            models[batch] = Model(sh, seed=70, batch=batch, positions=pos)   # same seed: same weights as the fleet's
+        kc, vc = base.kc.clone(), base.vc.clone()
+        hout = torch.empty((41, sh.hidden), device="cuda", dtype=torch.float32)
+        logits = torch.empty((41, sh.vocab), device="cuda", dtype=torch.float32)
+        stream = torch.cuda.current_stream().cuda_stream
+        torch.cuda.synchronize()
+        free0 = torch.cuda.mem_get_info()[0]
+        results = []
+        for batch in sizes:
+            m = models[batch]
+            kc.copy_(m.kc); vc.copy_(m.vc)
+            hout.fill_(float("nan")); logits.fill_(float("nan"))
+            F.fleet_decode_step(f, batch, m.hidden, None, kc, vc, m.pos, hout, logits, stream)
+            torch.cuda.synchronize()
+            assert torch.cuda.mem_get_info()[0] >= free0, f"device memory was allocated by the step of batch {batch}"
+            st = F.fleet_last_status(f)
+            assert st["code"] == 0, st
+            results.append((batch, hout.cpu().numpy(), logits.cpu().numpy()))
+        for batch, ho_g, lg_g in results:
+            print(f"  step with batch {batch}", flush=True)
+            (ho, lg), _, _ = models[batch].run_oracle()
+            assert_close(ho_g[:batch], ho, f"hidden_out batch {batch}")
+            assert_close(lg_g[:batch], lg, f"logits batch {batch}")
+            assert np.isnan(ho_g[batch:]).all() and np.isnan(lg_g[batch:]).all(), "rows beyond the batch were written"
+    finally:
+        F.fleet_destroy(f)
+
+
+def test_step_without_logits_skips_the_lm_head():
+    """logits == NULL: the step ends after the last layer and the final stage (hidden_out is
+    written, no LM-head task runs); with a buffer the same fleet computes the logits again."""
+    sh = si.reduced_shape(max_batch=3, max_seq=80, n_layers=2, vocab=1024)
+    m = Model(sh, seed=12, batch=3, positions=[0, 79, 33])
+    (ho, lg), _, _ = m.run_oracle()
+    f = F.fleet_create(sh.asdict(), m.w, 0, 0, F.FLAG_TIMING)
+    try:
+        stream = torch.cuda.current_stream().cuda_stream
+        hout = torch.full((3, sh.hidden), float("nan"), device="cuda", dtype=torch.float32)
+        F.fleet_decode_step(f, 3, m.hidden, None, m.kc.clone(), m.vc.clone(), m.pos, hout, None, stream)
+        assert F.fleet_last_status(f)["code"] == 0
+        assert_close(hout.cpu().numpy(), ho, "hidden_out without logits")
+        g = F.parse_graph(F.fleet_graph_dump(f, 3))
+        lm_op = [i for i, o in enumerate(g["ops"]) if o[13] == 5][0]
+        ran = set(F.fleet_trace_read(f)[:, 0].tolist())
+        assert not any(g["tasks"][t, 0] == lm_op for t in ran), "an LM-head task ran"
+        logits = torch.full((3, sh.vocab), float("nan"), device="cuda", dtype=torch.float32)
+        F.fleet_decode_step(f, 3, m.hidden, None, m.kc.clone(), m.vc.clone(), m.pos, hout, logits, stream)
+        assert F.fleet_last_status(f)["code"] == 0
+        assert_close(logits.cpu().numpy(), lg, "logits")
+    finally:
+        F.fleet_destroy(f)
+
+
+def test_fma_switch_is_latched_at_create(monkeypatch):
+    """fleet_create reads FLEET_FMA_MAX_BATCH once; changing it afterwards changes neither the
+    graphs nor the weights they read (an FMA fleet has no packed copies to fall back on)."""
+    monkeypatch.setenv("FLEET_FMA_MAX_BATCH", "8")
+    sh = si.reduced_shape(max_batch=6, max_seq=64, n_layers=1, vocab=512)
+    m = Model(sh, seed=13, batch=6, positions=[0, 63, 5, 17, 40, 41])
+    f = F.fleet_create(sh.asdict(), m.w, 0, 0, 0)
+    monkeypatch.setenv("FLEET_FMA_MAX_BATCH", "0")
+    try:
+        assert F.parse_graph(F.fleet_graph_dump(f, 6))["header"]["path"] == 0
+        (ho, lg), _, _ = m.run_oracle()
+        got = m.run_gpu(fleet=f)
+        assert_close(got[0], ho, "hidden_out")
+        assert_close(got[1], lg, "logits")
+    finally:
+        F.fleet_destroy(f)
+
+
+def test_packed_only_fleet_runs_without_the_callers_matrices():
+    """FLEET_FLAG_PACKED_ONLY: every batch size runs the MFMA kernels on the library's packed
+    copy, so the caller's GEMM matrices may be freed (here: overwritten) after fleet_create."""
+    sh = si.reduced_shape(max_batch=4, max_seq=64, n_layers=2, vocab=512)
+    m = Model(sh, seed=14, batch=4, positions=[0, 63, 5, 17])
+    w = {k: ([t.clone() for t in v] if isinstance(v, list) else v.clone()) for k, v in m.w.items()}
+    f = F.fleet_create(sh.asdict(), w, 0, 0, F.FLAG_PACKED_ONLY)
+    try:
+        for k in ("wqkv", "wo", "wgu", "wdown"):
+            for t in w[k]:
+                t.zero_()
+        w["lm_head"].zero_()
+        torch.cuda.synchronize()
+        for batch in (1, 4):
+            assert F.parse_graph(F.fleet_graph_dump(f, batch))["header"]["path"] == 1
+            mb = Model(sh, seed=14, batch=batch, positions=[0, 63, 5, 17][:batch])
+            (ho, lg), _, _ = mb.run_oracle()
+            got = mb.run_gpu(fleet=f)
             assert_close(got[0], ho, f"hidden_out batch {batch}")
             assert_close(got[1], lg, f"logits batch {batch}")
     finally:
         F.fleet_destroy(f)
+
+
+@pytest.mark.parametrize("batch,tile_m,sched", [(128, 0, 0), (100, 0, 0), (128, 16, 0), (128, 0, 1), (128, 32, 2)])
+def test_batch_above_64_runs_in_several_m_tiles(batch, tile_m, sched):
+    """Batches of 65 to 128 sequences: two 64-row m-tiles per GEMM with the whole-batch tile
+    height (or the given height), one attention task per (sequence, kv head)."""
+    print(f"decode 2 layers batch={batch} tile_m={tile_m} sched={sched}", flush=True)
+    sh = si.reduced_shape(max_batch=batch, max_seq=200, n_layers=2, vocab=1024)
+    pos = np.random.default_rng(batch + tile_m).integers(0, 200, batch).astype(np.int32)
+    pos[0], pos[1] = 0, 199
+    m = Model(sh, seed=15, batch=batch, positions=pos)
+    (ho, lg), k, v = m.run_oracle()
+    got = m.run_gpu(sched, tile_m, 0)
+    assert_close(got[0], ho, "hidden_out")
+    assert_close(got[1], lg, "logits")
+    check_new_kv(m, got[2], got[3], k, v)
 
 
 def test_embedding_gather_input():

@@ -20,6 +20,10 @@ from gpu_common import TOL, assert_close, rms
 pytestmark = pytest.mark.gpu
 
 L = 36
+# Free-running over 36 layers the kernel may differ from the oracle by as much as the oracle
+# differs from itself when only its fp32 summation order is reversed, times this factor
+# (measured ratios on MI355X: 0.8 to 1.2 over all the configurations below).
+ENVELOPE_FACTOR = 1.5
 
 
 @pytest.fixture(scope="module")
@@ -126,7 +130,8 @@ def _check(c, sched, tile_m, flags=0, free_running=True):
         el = np.abs(logits.index_select(0, idx).cpu().numpy() - lg).max() / rms(lg)
         print(f"  free-running max|err|/RMS: hidden {eh:.3e} logits {el:.3e}; oracle vs its own reversed "
               f"summation order: hidden {env_h:.3e} logits {env_l:.3e}", flush=True)
-        assert eh <= max(3 * env_h, TOL) and el <= max(3 * env_l, TOL)
+        print(f"  ratio to the envelope: hidden {eh / env_h:.2f} logits {el / env_l:.2f}", flush=True)
+        assert eh <= max(ENVELOPE_FACTOR * env_h, TOL) and el <= max(ENVELOPE_FACTOR * env_l, TOL)
         return hout, logits
     return None, None
 
@@ -150,6 +155,55 @@ def test_batch64_kv4096_cooperative_and_unaware(weights):
     # same tiles, same in-tile reduction order, two task-to-worker maps: identical bits
     assert torch.equal(h0, h1) and torch.equal(l0, l1)
     _check(c, F.SCHED_COOPERATIVE, 0, free_running=False)
+
+
+@pytest.mark.parametrize("batch,sched,tile_m,fma_max", [
+    (32, F.SCHED_UNAWARE, 0, None),      # chiplet-unaware schedule with the whole-batch tile
+    (32, F.SCHED_MSPLIT, 16, None),      # M-split over 16-row tiles
+    (2, F.SCHED_COOPERATIVE, 0, None),   # FMA GEMV kernel with two batch rows
+    (16, F.SCHED_COOPERATIVE, 0, None),  # MFMA kernel, one full 16-row block
+    (8, F.SCHED_COOPERATIVE, 0, 8),      # FMA GEMV kernel with eight batch rows
+    (4, F.SCHED_COOPERATIVE, 0, 8),      # FMA GEMV kernel with four batch rows
+])
+def test_other_schedules_and_kernel_flavours_at_full_depth(weights, monkeypatch, batch, sched, tile_m, fma_max):
+    """Teacher-forced 36-layer comparison with the oracle (2e-2 x RMS per layer and on the
+    logits) for the schedule / kernel-flavour combinations the other tests of this file do not
+    reach: every persistent-kernel variant meets the oracle at the full model size."""
+    if fma_max is not None:
+        monkeypatch.setenv("FLEET_FMA_MAX_BATCH", str(fma_max))
+    rows = sorted({0, batch // 2, batch - 1})
+    c = _case(weights, batch, 1024, 2048, seed=3, rows=rows)
+    print(f"batch {batch} sched {sched} tile_m {tile_m} fma_max {fma_max}: positions {c['pos_h'].tolist()}", flush=True)
+    _check(c, sched, tile_m, free_running=False)
+
+
+def test_timeout_aborts_a_full_size_step(weights, monkeypatch):
+    """With a time limit of half a microsecond against a 36-layer batch-32 step (its stages last
+    tens of microseconds) some dependency wait runs out: the step aborts on the device, every
+    worker leaves, the status says FLEET_ETIMEOUT with the event that was waited for, and the
+    same fleet geometry runs normally again afterwards."""
+    monkeypatch.setenv("FLEET_TIMEOUT_MS", "0.0005")
+    c = _case(weights, 32, 2048, 2048, seed=3, rows=[0])
+    sh = c["shape"]
+    f = F.fleet_create(sh.asdict(), c["w"], 0, 0, 0)
+    monkeypatch.delenv("FLEET_TIMEOUT_MS")
+    try:
+        hout = torch.zeros((32, sh.hidden), device="cuda")
+        logits = torch.zeros((32, sh.vocab), device="cuda")
+        F.fleet_decode_step(f, 32, c["hidden"], None, c["kc"], c["vc"], c["pos"], hout, logits,
+                            torch.cuda.current_stream().cuda_stream)
+        st = F.fleet_last_status(f)
+        print("status with a 0.5 us limit:", st, flush=True)
+        assert st["code"] == -4 and st["event"] >= 0 and st["observed"] < st["needed"]
+    finally:
+        F.fleet_destroy(f)
+    f = F.fleet_create(sh.asdict(), c["w"], 0, 0, 0)
+    try:
+        F.fleet_decode_step(f, 32, c["hidden"], None, c["kc"], c["vc"], c["pos"], hout, logits,
+                            torch.cuda.current_stream().cuda_stream)
+        assert F.fleet_last_status(f)["code"] == 0 and torch.isfinite(logits).all()
+    finally:
+        F.fleet_destroy(f)
 
 
 @pytest.mark.parametrize("batch,kv_lo,kv_hi,reps,sched,tile_m", [
