@@ -40,7 +40,9 @@ enum fleet_err {
   FLEET_EHIP = -3,     /* a HIP call failed; see fleet_last_status().hip_error   */
   FLEET_ETIMEOUT = -4, /* a dependency wait ran out of time; the step aborted    */
   FLEET_ESMALL = -5,   /* output buffer too small; *len holds the needed size    */
-  FLEET_EDEVICE = -6   /* the device cannot hold the persistent grid             */
+  FLEET_EDEVICE = -6,  /* the device cannot hold the persistent grid             */
+  FLEET_ETOOBIG = -7   /* fleet_decode_step_static: the step needs more working
+                          memory than FLEET_STATIC_SCRATCH_BYTES                  */
 };
 
 /* Task scheduling (paper section 3.2 and Figure "tiling"). */
@@ -193,6 +195,26 @@ int fleet_decode_layers(fleet_t *f, int32_t batch, int32_t layer_begin, int32_t 
 /* fleet_destroy: free everything the library allocated.  NULL is accepted. */
 int fleet_destroy(fleet_t *f);
 
+/*
+ * fleet_decode_step_static: fleet_decode_step for callers that cannot allocate device
+ * memory and want none held per fleet_t for the step's working set (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc).  The working memory of the
+ * step -- activations, split-KV and split-K partial sums, dependency counters, status block
+ * -- lives in a static device array of FLEET_STATIC_SCRATCH_BYTES that the library's code
+ * object carries (every GPU the library runs on holds it until the process ends) instead
+ * of the fleet's own allocation.  Arguments and results as fleet_decode_step; the results
+ * are bit-identical to it.  A step whose working memory exceeds the array (large batches on
+ * the MFMA path with split-K partial sums; the Qwen3-8B shape fits up to batch 16) is
+ * refused with FLEET_ETOOBIG before anything is launched.  The call itself allocates
+ * nothing, frees nothing and copies nothing from the host; counters and status are cleared
+ * by a kernel at the start of every call.  All calls on one GPU share the array: calls
+ * that overlap on one GPU (two streams, two fleets, two threads) race; calls on one stream
+ * are safe.  fleet_last_status reports on the last step launched either way.
+ */
+#define FLEET_STATIC_SCRATCH_BYTES (32u << 20)
+int fleet_decode_step_static(fleet_t *f, int32_t batch, const void *hidden_in, const int32_t *tokens,
+                             void *k_cache, void *v_cache, const int32_t *positions,
+                             float *hidden_out, float *logits, void *stream);
 
 /*
  * fleet_decode_step_paged: fleet_decode_step over a paged KV cache.

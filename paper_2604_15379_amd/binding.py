@@ -19,10 +19,11 @@ SCHED_COOPERATIVE, SCHED_UNAWARE, SCHED_MSPLIT = 0, 1, 2
 FLAG_TRACE, FLAG_SINGLE_LEVEL, FLAG_SEPARATE_NORM, FLAG_CHAINED, FLAG_TIMING = 1, 2, 4, 8, 16
 FLAG_NO_SPLITK, FLAG_NO_STREAM, FLAG_NO_RESIDENT, FLAG_UNFUSED_SILU, FLAG_LEADER_RELAY = 32, 64, 128, 256, 512
 FLAG_PACKED_ONLY = 1024
+STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = (
     "fleet_create", "fleet_decode_step", "fleet_decode_step_paged", "fleet_decode_layers",
-    "fleet_decode_tokens", "fleet_destroy",
+    "fleet_decode_tokens", "fleet_destroy", "fleet_decode_step_static",
     "fleet_gemm",
     "fleet_graph_build", "fleet_graph_dump", "fleet_trace_read", "fleet_last_status",
     "fleet_device_probe", "fleet_copy", "fleet_weight_bytes", "fleet_weight_bytes_per_xcd",
@@ -140,6 +141,15 @@ def fleet_decode_step(f: Fleet, batch: int, hidden_in, tokens, k_cache, v_cache,
                                           _ptr(hidden_out), _ptr(logits), C.c_void_p(stream))
     if rc != 0:
         raise FleetError(rc, "fleet_decode_step")
+
+
+def fleet_decode_step_static(f: Fleet, batch: int, hidden_in, tokens, k_cache, v_cache, positions,
+                             hidden_out, logits, stream=0) -> None:
+    rc = load_library().fleet_decode_step_static(f.handle, C.c_int32(batch), _ptr(hidden_in), _ptr(tokens),
+                                                 _ptr(k_cache), _ptr(v_cache), _ptr(positions),
+                                                 _ptr(hidden_out), _ptr(logits), C.c_void_p(stream))
+    if rc != 0:
+        raise FleetError(rc, "fleet_decode_step_static")
 
 
 def fleet_decode_layers(f: Fleet, batch: int, layer_begin: int, layer_end: int, x_in, k_cache,

@@ -16,6 +16,11 @@
 #include "graph.hpp"
 #include "kernels.hip.inc"
 
+// Workspace of fleet_decode_step_static, the entry point that allocates nothing: the
+// activations, partial sums, counters and status block of one step live in this array
+// instead of the fleet's own allocation.  Host code never uses the array's name as an
+// address: the device address is looked up once per device (static_workspace()).
+static __device__ __align__(256) unsigned char fleet_static_scratch[FLEET_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -146,6 +151,7 @@ int launch_persistent(DevGraph* dg, dev::Params& P, int n_cu, hipStream_t st) {
 // Per-device, once: raise the kernels' dynamic LDS limit and check that one worker fits a CU.
 std::mutex g_dev_mutex;
 bool g_prepared[MAX_DEVICES] = {false};
+void* g_static_ws[MAX_DEVICES] = {nullptr};
 
 int prepare_kernel() {
   int dev_id = 0, lds = 0;
@@ -167,6 +173,22 @@ int prepare_kernel() {
   return FLEET_OK;
 }
 
+// Device address of the static workspace on the current device (every device holds its own
+// copy of the array at its own address); looked up once per device.
+int static_workspace(void** out) {
+  int dev_id = 0;
+  HIP_TRY(hipGetDevice(&dev_id));
+  if (dev_id < 0 || dev_id >= MAX_DEVICES) return FLEET_EDEVICE;
+  std::lock_guard<std::mutex> lock(g_dev_mutex);
+  if (!g_static_ws[dev_id]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(fleet_static_scratch)));
+    if (!p) return FLEET_EHIP;
+    g_static_ws[dev_id] = p;
+  }
+  *out = g_static_ws[dev_id];
+  return FLEET_OK;
+}
 
 int probe_device(DevInfo* info, int32_t* xcd_of_block_out, int n_blocks_req) {
   int rc = prepare_kernel();
@@ -408,6 +430,7 @@ struct StepArgs {
   int n_tokens = 0; int32_t* tokens_out = nullptr;   // n_tokens > 0: that many steps in one launch
   const KvPaging* paging = nullptr;
   const float* x_in = nullptr;                       // layer ranges: residual stream to start from
+  bool static_ws = false;                            // work in the static workspace
 };
 
 // No allocation, no host-device copy, no synchronisation: kernels (and, for layer ranges,
@@ -422,7 +445,15 @@ int run_layers(fleet* f, const StepArgs& a, hipStream_t st) {
   if (!dg) return FLEET_EINVAL;
   const Graph& g = dg->g;
   Work w;
+  if (a.static_ws) {
+    if (work_layout(f, dg, nullptr, nullptr) > (size_t)FLEET_STATIC_SCRATCH_BYTES) return FLEET_ETOOBIG;
+    void* base = nullptr;
+    int rc = static_workspace(&base);   // looked up by fleet_create on this device: a table read here
+    if (rc) return rc;
+    work_layout(f, dg, (char*)base, &w);
+  } else {
     work_layout(f, dg, f->work, &w);
+  }
   const int L = f->shape.n_layers, nm = n_marks(L), nx = f->info.n_xcd;
   dev::Params P;
   memset(&P, 0, sizeof(P));
@@ -480,6 +511,7 @@ const char* fleet_strerror(int code) {
     case FLEET_ETIMEOUT: return "dependency wait timed out; step aborted";
     case FLEET_ESMALL: return "buffer too small";
     case FLEET_EDEVICE: return "device cannot hold the persistent grid";
+    case FLEET_ETOOBIG: return "the step needs more working memory than the static workspace holds";
     default: return "unknown error";
   }
 }
@@ -513,6 +545,10 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
   if ((rc = probe_device(&f->info, nullptr, 0))) return rc;
   for (int x = 0; x < f->info.n_xcd; ++x)
     if (f->info.per_xcd[x] == 0) return FLEET_EDEVICE;
+  {   // the static workspace's address on this device, for fleet_decode_step_static
+    void* ws = nullptr;
+    if ((rc = static_workspace(&ws))) return rc;
+  }
 
   const size_t H = shape->hidden, F = shape->ffn;
   const size_t NQKV = (size_t)(shape->n_q_heads + 2 * shape->n_kv_heads) * shape->head_dim;
@@ -593,6 +629,17 @@ int fleet_decode_step(fleet_t* f, int32_t batch, const void* hidden_in, const in
   return run_layers(f, a, (hipStream_t)stream);
 }
 
+int fleet_decode_step_static(fleet_t* f, int32_t batch, const void* hidden_in, const int32_t* tokens, void* k_cache,
+                             void* v_cache, const int32_t* positions, float* hidden_out, float* logits, void* stream) {
+  int rc = check_step_args(f, batch, hidden_in, tokens, k_cache, v_cache, positions, hidden_out);
+  if (rc) return rc;
+  StepArgs a;
+  a.batch = batch; a.layer_end = f->shape.n_layers; a.with_ingest = a.with_final = true;
+  a.hidden_in = hidden_in; a.tokens = tokens; a.k_cache = k_cache; a.v_cache = v_cache; a.positions = positions;
+  a.hidden_out = hidden_out; a.logits = f->shape.vocab > 0 ? logits : nullptr;
+  a.static_ws = true;
+  return run_layers(f, a, (hipStream_t)stream);
+}
 
 int fleet_decode_layers(fleet_t* f, int32_t batch, int32_t layer_begin, int32_t layer_end, const float* x_in,
                         void* k_cache, void* v_cache, const int32_t* positions, float* x_out, float* logits,
