@@ -59,6 +59,8 @@ def parse():
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--seed", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", dest="sweep", action="store_false",
+                    help="skip the extra workloads (batch 8 / 32 / 64) reported under 'sweep'")
     ap.add_argument("--gemm-sweep", action="store_true",
                     help="isolated skinny-GEMM sweep at the Qwen3-8B shapes (one JSON line per case)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
@@ -210,48 +212,56 @@ def main():
     if a.tokens_per_launch > 0:
         tokens_per_launch(a)
         return
-    B = a.batch
-    shape = si.qwen3_8b_shape(max_batch=B, max_seq=a.kv + 1, n_layers=a.layers)
     g = si.Gen(a.seed, "cuda")
-    w = si.make_weights(shape, g)
-    hidden = si.make_hidden(shape, B, g)
-    kc, vc = si.make_kv_cache(shape, g)
-    if a.kv_min > 0:
-        pos_host = g.randint(a.kv_min, a.kv, B).cpu().numpy().astype(np.int32)
-    else:
-        pos_host = np.full(B, a.kv, np.int32)
-    pos = torch.tensor(pos_host, device="cuda")
-    hout = torch.empty((B, shape.hidden), device="cuda", dtype=torch.float32)
-    logits = torch.empty((B, shape.vocab), device="cuda", dtype=torch.float32)
-    f = F.fleet_create(shape.asdict(), w, a.sched, a.tile_m, a.flags)
-    stream = torch.cuda.current_stream().cuda_stream
+    w = si.make_weights(si.qwen3_8b_shape(max_batch=1, max_seq=2, n_layers=a.layers), g)
 
-    def step():
-        F.fleet_decode_step(f, B, hidden, None, kc, vc, pos, hout, logits, stream)
+    def time_config(batch, kv, kv_min, sched, tile_m, flags, steps, warmup):
+        """One workload: seeded inputs resident in HBM, `warmup` untimed steps, `steps` timed ones
+        between two events on the launch stream."""
+        shape = si.qwen3_8b_shape(max_batch=batch, max_seq=kv + 1, n_layers=a.layers)
+        gi = si.Gen(a.seed + 7919 * batch, "cuda")
+        hidden = si.make_hidden(shape, batch, gi)
+        kc, vc = si.make_kv_cache(shape, gi)
+        pos_host = gi.randint(kv_min, kv, batch).cpu().numpy().astype(np.int32) if kv_min > 0 else np.full(batch, kv, np.int32)
+        pos = torch.tensor(pos_host, device="cuda")
+        hout = torch.empty((batch, shape.hidden), device="cuda", dtype=torch.float32)
+        logits = torch.empty((batch, shape.vocab), device="cuda", dtype=torch.float32)
+        f = F.fleet_create(shape.asdict(), w, sched, tile_m, flags)
+        stream = torch.cuda.current_stream().cuda_stream
+        try:
+            for _ in range(warmup):
+                F.fleet_decode_step(f, batch, hidden, None, kc, vc, pos, hout, logits, stream)
+            torch.cuda.synchronize()
+            st = F.fleet_last_status(f)
+            if st["code"] != 0:
+                raise SystemExit(f"decode step failed: {st}")
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(steps):
+                F.fleet_decode_step(f, batch, hidden, None, kc, vc, pos, hout, logits, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / steps
+            st = F.fleet_last_status(f)
+            if st["code"] != 0 or not torch.isfinite(logits).all():
+                raise SystemExit(f"decode step failed: {st}")
+        finally:
+            F.fleet_destroy(f)
+        step_bytes = F.fleet_step_bytes(shape.asdict(), batch, pos_host)
+        return dict(ms=ms, step_bytes=step_bytes, gbps=step_bytes / (ms * 1e-3) / 1e9, shape=shape, hidden=hidden,
+                    workers=st["workers"])
 
-    for _ in range(a.warmup):
-        step()
-    torch.cuda.synchronize()
-    st = F.fleet_last_status(f)
-    if st["code"] != 0:
-        raise SystemExit(f"decode step failed: {st}")
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(a.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / a.steps
-    st = F.fleet_last_status(f)
-    if st["code"] != 0 or not torch.isfinite(logits).all():
-        raise SystemExit(f"decode step failed: {st}")
-
-    step_bytes = F.fleet_step_bytes(shape.asdict(), B, pos_host)
+    B = a.batch
+    r = time_config(B, a.kv, a.kv_min, a.sched, a.tile_m, a.flags, a.steps, a.warmup)
+    ms, step_bytes, gbps, shape = r["ms"], r["step_bytes"], r["gbps"], r["shape"]
     traffic = a.traffic_bytes
+    traffic_source = "--traffic-bytes" if traffic is not None else None
     if traffic is None and a.layers == 36 and a.seed == 2:
         traffic = MEASURED_TRAFFIC.get((B, a.kv, a.kv_min, a.sched, a.tile_m, a.flags))
-    gbps = step_bytes / (ms * 1e-3) / 1e9
+        if traffic is not None:
+            traffic_source = ("constant from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes in profiles/ "
+                              "(not measured in this run)")
     out = {
         "metric": "decode_step_latency_us", "value": ms * 1e3, "unit": "us", "n_gpus": 1,
         "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": False,
@@ -261,15 +271,26 @@ def main():
                    "batch": B, "kv_len": a.kv, "sched_mode": ["cooperative", "unaware", "m-split"][a.sched],
                    "tile_m": a.tile_m, "flags": a.flags, "tokens_per_s": B / (ms * 1e-3)},
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": gbps / HBM_PEAK_GBPS, "traffic": traffic,
+                     "frac": gbps / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_bytes": step_bytes,
                      "kernel": "fleet_persistent_kernel (one launch per step)"},
-        "l2_hit_model": F.fleet_l2_hit_model(B, a.tile_m or 16 * ((B + 15) // 16) if B > 2 else B or 1, 32),
-        "workers_per_xcd": st["workers"],
+        "l2_hit_model": F.fleet_l2_hit_model(B, a.tile_m, 32) if B > 2 else 0.0,
+        "workers_per_xcd": r["workers"],
     }
+    if a.sweep:
+        # the other workloads of the metric (batch 8 / 32 with ragged KV 1024..2048, batch 64 with KV
+        # 4096, cooperative against chiplet-unaware at the paper's 16-row tiles), fewer steps each
+        out["sweep"] = []
+        for (b, kv, kv_min, sched, tile_m, steps) in ((8, 2048, 1024, 0, 0, 10), (32, 2048, 1024, 0, 0, 10),
+                                                      (64, 4096, 0, 0, 0, 5), (64, 4096, 0, 0, 16, 5),
+                                                      (64, 4096, 0, 1, 16, 5)):
+            t = time_config(b, kv, kv_min, sched, tile_m, 0, steps, 2)
+            out["sweep"].append({"batch": b, "kv": kv, "kv_min": kv_min or kv,
+                                 "sched": ["cooperative", "unaware", "m-split"][sched], "tile_m": tile_m,
+                                 "ms_per_step": t["ms"], "algorithmic_bytes": t["step_bytes"],
+                                 "GBps": t["gbps"], "frac": t["gbps"] / HBM_PEAK_GBPS, "steps": steps})
     if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(shape, w, hidden, B, a.kv, a.seed)
-    F.fleet_destroy(f)
+        out["cpu_baseline"] = cpu_baseline(shape, w, r["hidden"], B, a.kv, a.seed)
     print(json.dumps(out))
 
 

@@ -75,6 +75,9 @@ enum fleet_flags {
   FLEET_FLAG_LEADER_RELAY = 512,/* only the leader (rank 0) of an XCD polls the device counter
                                   and relays it to a word per follower, instead of every
                                   worker polling one of the per-XCD copies of the counter */
+  FLEET_FLAG_NT_STORES = 2048,  /* partial sums handed over inside one XCD (split-K GEMM tiles,
+                                  split-KV attention) are stored with the non-temporal hint
+                                  (section 3.2, cache-modifier flavours: nt stores on/off)  */
   FLEET_FLAG_PACKED_ONLY = 1024 /* every batch size runs the MFMA kernels on the library's
                                   packed weight copy: the caller may free wqkv, wo, wgu, wdown
                                   and lm_head once fleet_create has returned (one copy of
