@@ -72,9 +72,6 @@ enum fleet_flags {
   FLEET_FLAG_UNFUSED_SILU = 256,/* gate|up GEMM stores its fp32 sums; SiLU(gate) x up runs as
                                   a stage of CU-tasks of its own (section 3.2, operator
                                   fusion ablation)                                      */
-  FLEET_FLAG_LEADER_RELAY = 512,/* only the leader (rank 0) of an XCD polls the device counter
-                                  and relays it to a word per follower, instead of every
-                                  worker polling one of the per-XCD copies of the counter */
   FLEET_FLAG_NT_STORES = 2048,  /* partial sums handed over inside one XCD (split-K GEMM tiles,
                                   split-KV attention) are stored with the non-temporal hint
                                   (section 3.2, cache-modifier flavours: nt stores on/off)  */
@@ -150,7 +147,7 @@ typedef struct {
  * sums of split-K GEMM tiles: k-slices x padded batch x the widest split output, fp32, once
  * per XCD under the XCD-aware schedules (8 x 8 MB for the Qwen3-8B shape at batch 64).
  * Requirements: head_dim == 128, n_q_heads a multiple of n_kv_heads with ratio <= 4, vocab
- * a multiple of 16, hidden and ffn multiples of 32; every weight matrix smaller than 2 GiB
+ * a multiple of 16, hidden and ffn multiples of 32, at most 120 layers; every weight matrix smaller than 2 GiB
  * and max_seq * 256 < 2^31 (the kernels use 32-bit byte offsets inside a matrix and inside
  * one (sequence, kv head) stream of the cache).  Anything else: FLEET_EINVAL.
  */
@@ -267,7 +264,7 @@ int fleet_decode_tokens(fleet_t *f, int32_t batch, int32_t *tokens, void *k_cach
  *   sched_mode, tile_m  as in fleet_shape_t
  *   elapsed_ms  HOST float or NULL: time of the one kernel launch that runs all
  *             reps, measured with HIP events on `stream`
- * K a multiple of 32, N of 16, N * K * 2 < 2^31, 1 <= B <= 128.  Synchronous: returns after the
+ * K a multiple of 32, N of 16, N * K * 2 < 2^31, 1 <= B <= 128, 1 <= reps <= 1024.  Synchronous: returns after the
  * kernel has finished (it allocates and frees its own descriptors and, on the MFMA
  * path, packed copies of x and of every weight copy).  Repetitions are independent
  * of each other unless FLEET_FLAG_CHAINED is set; with a split-K plan a repetition

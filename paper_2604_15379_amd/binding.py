@@ -17,7 +17,7 @@ _LIB_PATH = os.path.join(_PKG, "libfleet.so")
 
 SCHED_COOPERATIVE, SCHED_UNAWARE, SCHED_MSPLIT = 0, 1, 2
 FLAG_TRACE, FLAG_SINGLE_LEVEL, FLAG_SEPARATE_NORM, FLAG_CHAINED, FLAG_TIMING = 1, 2, 4, 8, 16
-FLAG_NO_SPLITK, FLAG_NO_STREAM, FLAG_NO_RESIDENT, FLAG_UNFUSED_SILU, FLAG_LEADER_RELAY = 32, 64, 128, 256, 512
+FLAG_NO_SPLITK, FLAG_NO_STREAM, FLAG_NO_RESIDENT, FLAG_UNFUSED_SILU = 32, 64, 128, 256
 FLAG_PACKED_ONLY, FLAG_NT_STORES = 1024, 2048
 STATIC_SCRATCH_BYTES = 32 << 20
 

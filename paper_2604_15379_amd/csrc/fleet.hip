@@ -50,8 +50,6 @@ struct DevGraph {
   int32_t *ops = nullptr, *tasks = nullptr, *events = nullptr, *qoff = nullptr, *qents = nullptr;
   int32_t* fat = nullptr;   // [n_tasks][FAT_WORDS]: task words, op words, weight pointers, id
   int ctr_words = 0, gcnt_base = 0;
-  // memo of wait_event_range for the last queue slice launched
-  int memo_begin[dev::MAX_XCD] = {-1, -1, -1, -1, -1, -1, -1, -1}, memo_end[dev::MAX_XCD] = {0}, memo_first = 0, memo_last = -1;
   ~DevGraph() {
     for (void* p : {(void*)ops, (void*)tasks, (void*)events, (void*)qoff, (void*)qents, (void*)fat})
       if (p) (void)hipFree(p);
@@ -115,34 +113,9 @@ int variant_for(int path, int batch, int tile_m) {
   if (path == P_FMA) return batch <= 1 ? 0 : batch <= 2 ? 1 : batch <= 4 ? 2 : 3;
   return tile_m <= 16 ? 4 : tile_m <= 32 ? 5 : 6;
 }
-// range of events that tasks of the launched queue slices wait for (stages of the slices)
-void wait_event_range(const Graph& g, dev::Params& P, int n_xcd) {
-  int lo = 1 << 30, hi = -1;
-  for (int x = 0; x < n_xcd; ++x)
-    for (int qi = P.q_begin[x]; qi < P.q_end[x]; ++qi) {
-      const int32_t* e = &g.qents[((size_t)g.qoff[x] + qi) * QENT_WORDS];
-      for (int t = e[Q_FIRST]; t < e[Q_FIRST] + e[Q_COUNT]; ++t) {
-        const int w = g.tasks[(size_t)t * TASK_WORDS + T_WAIT_EVENT];
-        if (w >= 0) { lo = std::min(lo, w); hi = std::max(hi, w); }
-      }
-    }
-  P.first_wait_event = hi >= 0 ? lo : 0;
-  P.last_wait_event = hi;
-}
-
 int launch_persistent(DevGraph* dg, dev::Params& P, int n_cu, hipStream_t st) {
   const Graph& g = dg->g;
   const int v = variant_for(g.header[H_PATH], g.header[H_BATCH], g.header[H_TILE_M]);
-  const int nx = g.header[H_N_XCD];
-  bool same = true;
-  for (int x = 0; x < nx; ++x) same = same && dg->memo_begin[x] == P.q_begin[x] && dg->memo_end[x] == P.q_end[x];
-  if (!same) {
-    wait_event_range(g, P, nx);
-    for (int x = 0; x < nx; ++x) { dg->memo_begin[x] = P.q_begin[x]; dg->memo_end[x] = P.q_end[x]; }
-    dg->memo_first = P.first_wait_event; dg->memo_last = P.last_wait_event;
-  } else {
-    P.first_wait_event = dg->memo_first; P.last_wait_event = dg->memo_last;
-  }
   void* args[] = {(void*)&P};
   HIP_TRY(hipLaunchKernel(kernel_variant(v, P.page_size > 0), dim3(n_cu), dim3(dev::WG), args, LDS_BYTES, st));
   return FLEET_OK;
@@ -378,10 +351,10 @@ int upload_graph(DevGraph* dg, const fleet* f, const void* const* gemm_copies, i
     }
   if ((rc = upload(&dg->fat, fat.data(), fat.size() * 4))) return rc;
   // counter block: G[e], L[x][e], one arrival counter per (sequence, kv head) for the split-KV
-  // merge, one relay word per worker on its own cache line, the per-XCD copies of the device
-  // counters (rows on their own cache lines), and (MFMA graphs) the arrival counters of
-  // split-K GEMM tiles
-  dg->gcnt_base = dev::C_EVENTS + g.n_events() * (1 + n_xcd) + dev::N_PAIR + n_xcd * dev::RELAY_SLOTS * dev::RELAY_STRIDE +
+  // merge, the per-XCD copies of the device counters (rows on their own cache lines), and
+  // (MFMA graphs) the arrival counters of split-K GEMM tiles
+  if (g.n_events() > dev::ECACHE) return FLEET_EINVAL;   // the kernel keeps one table entry per event in LDS
+  dg->gcnt_base = dev::C_EVENTS + g.n_events() * (1 + n_xcd) + dev::N_PAIR +
                   dev::COPY_GROUPS * n_xcd * ((g.n_events() + 31) & ~31);
   dg->ctr_words = dg->gcnt_base + (g.header[H_PATH] == P_MFMA ? dev::GEMM_CNT_WORDS : 0);
   return FLEET_OK;
@@ -397,7 +370,7 @@ int launch(dev::Params& P, DevGraph* dg, int n_cu, int preset_event, hipStream_t
     preset_val = 0x40000000u;   // satisfied whatever the threshold
   }
   const int nE = dg->g.n_events(), nx = dg->g.header[H_N_XCD], cstride = (nE + 31) & ~31;
-  const int cbase = dev::C_EVENTS + nE * (1 + nx) + dev::N_PAIR + nx * dev::RELAY_SLOTS * dev::RELAY_STRIDE;
+  const int cbase = dev::C_EVENTS + nE * (1 + nx) + dev::N_PAIR;
   hipLaunchKernelGGL(fleet_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, st, P.ctr, words, preset_word,
                      preset_val, P.status, cbase, cstride, dev::COPY_GROUPS * nx, preset_event);
   return launch_persistent(dg, P, n_cu, st);
@@ -753,7 +726,7 @@ int fleet_trace_read(fleet_t* f, void* buf, size_t* len) {
 
 int fleet_gemm(int32_t B, int32_t K, int32_t N, const void* x, const void* const* w_copies, int32_t n_copies, float* y,
                int32_t sched_mode, int32_t tile_m, int32_t flags, int32_t reps, void* stream, float* elapsed_ms) {
-  if (B < 1 || B > MAX_BATCH || K < 32 || K % 32 || N < 16 || N % 16 || !x || !w_copies || n_copies < 1 || !y || reps < 1 || reps > 4096)
+  if (B < 1 || B > MAX_BATCH || K < 32 || K % 32 || N < 16 || N % 16 || !x || !w_copies || n_copies < 1 || !y || reps < 1 || reps > dev::ECACHE)
     return FLEET_EINVAL;
   if ((int64_t)N * K * 2 >= (int64_t)1 << 31) return FLEET_EINVAL;   // 32-bit byte offsets inside a matrix
   if (sched_mode < FLEET_SCHED_COOPERATIVE || sched_mode > FLEET_SCHED_MSPLIT) return FLEET_EINVAL;

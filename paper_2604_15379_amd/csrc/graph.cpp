@@ -257,7 +257,7 @@ int attention_splits(int batch, int n_kv_heads, int n_workers, int max_seq) {
 }
 
 int check_shape(const fleet_shape_t& s) {
-  if (s.n_layers < 1 || s.hidden < 32 || s.ffn < 32 || s.n_q_heads < 1 || s.n_kv_heads < 1) return FLEET_EINVAL;
+  if (s.n_layers < 1 || s.n_layers > MAX_LAYERS || s.hidden < 32 || s.ffn < 32 || s.n_q_heads < 1 || s.n_kv_heads < 1) return FLEET_EINVAL;
   if (s.head_dim != 128) return FLEET_EINVAL;
   if (s.n_q_heads % s.n_kv_heads || s.n_q_heads / s.n_kv_heads > 4) return FLEET_EINVAL;
   if (s.hidden % 32 || s.ffn % 32) return FLEET_EINVAL;

@@ -114,6 +114,7 @@ int mfma_blocks(int tile_m);
 int fma_max_from_env();
 constexpr int MAX_TILE_ROWS = 64;   // batch rows one MFMA tile can hold (4 blocks of 16)
 constexpr int MAX_BATCH = 128;
+constexpr int MAX_LAYERS = 120;     // at most 8 events per layer: a graph stays within the 1024 entries of the kernels' event table
 // tile_m actually used for `batch` (0 = whole batch rounded up to 16, at most MAX_TILE_ROWS;
 // FMA path: batch)
 int resolve_tile_m(int batch, int tile_m, int fma_max);

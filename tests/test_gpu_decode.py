@@ -66,8 +66,7 @@ def test_fma_mfma_switch_moved_by_environment(monkeypatch, batch, fma_max):
                                                  (0, 0, F.FLAG_NO_SPLITK), (1, 16, F.FLAG_NO_SPLITK),
                                                  (0, 0, F.FLAG_NO_STREAM), (0, 0, F.FLAG_NO_RESIDENT),
                                                  (1, 0, F.FLAG_NO_RESIDENT), (0, 0, F.FLAG_UNFUSED_SILU),
-                                                 (1, 16, F.FLAG_UNFUSED_SILU), (0, 0, F.FLAG_LEADER_RELAY),
-                                                 (1, 0, F.FLAG_LEADER_RELAY), (0, 0, F.FLAG_NT_STORES),
+                                                 (1, 16, F.FLAG_UNFUSED_SILU), (0, 0, F.FLAG_NT_STORES),
                                                  (1, 16, F.FLAG_NT_STORES)])
 @pytest.mark.parametrize("batch", [2, 3, 40])      # FMA path, MFMA path with one and with three 16-row blocks
 def test_schedules_agree_with_oracle(batch, sched, tile_m, flags):
