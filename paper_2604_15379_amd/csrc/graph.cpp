@@ -189,22 +189,42 @@ std::vector<int32_t> Graph::serialize() const {
 
 int mfma_blocks(int tile_m) { return tile_m <= 16 ? 1 : tile_m <= 32 ? 2 : 4; }
 
-// Tile plan of an MFMA GEMM operator: G units per tile and KS k-slices, chosen so that the
-// tiles of one XCD's unit slice (ux units, m_tiles m-tiles each) keep its wpx workers equally
-// busy and the tiles are tall: minimise ceil(tiles / workers) * (G + 2) / KS -- a tile of G
-// units costs about G + 2, because the weight bytes a worker keeps in flight grow with G and
-// the activations are read once per tile -- then prefer more units per tile, then fewer
-// slices.  allow_split = false: one k-slice only.
+// Tile plan of an MFMA GEMM operator: G units per tile and KS k-slices for the tiles of one
+// XCD's unit slice (ux units, m_tiles m-tiles each, wpx workers), by a cost model fitted to
+// a sweep of plans on MI355X (integer arithmetic; times in ns, sizes in KB, rates in KB/us):
+//   * a worker streams a tile at the rate its bytes in flight allow -- (D - 1) rounds of
+//     G * nb row blocks of 8 KB, over a loaded latency of 3.8 us (2.5 us where several m-tiles
+//     share the weights through the L2) -- capped per CU (30, shared 45) and by the XCD's share
+//     of the memory bandwidth (700 per XCD over the workers that hold a tile, times the number
+//     of m-tiles that share a weight read);
+//   * a round costs 0.1 us per block of 16 batch rows (activation reads, MFMAs);
+//   * a tile costs 1 us on top (pipeline fill, cross-wave reduction, epilogue), a split-K tile
+//     3 us + 0.2 us per slice (partial sums out, arrival counter, the last arriver's reduction).
+// The worker with the most tiles decides (+10 % where the tiles do not divide evenly among
+// the workers).  Ties: more units per tile, then fewer slices.
+// allow_split = false: one k-slice only.
 MfmaPlan plan_mfma(int ux, int wpx, int K, int nb, int mt_blocks, int m_tiles, bool allow_split) {
   const int gmax = std::max(1, ((mt_blocks >= 4 || nb == 2) ? 6 : 8) / nb);
-  ux = std::max(1, ux); wpx = std::max(1, wpx);
+  const int depth = (mt_blocks >= 4 || (mt_blocks == 2 && nb == 1)) ? 3 : 4;   // operand rounds held (kernel: MfmaCfg::D)
+  ux = std::max(1, ux); wpx = std::max(1, wpx); m_tiles = std::max(1, m_tiles);
+  const bool shared = m_tiles > 1;
   MfmaPlan best{1, 1, 0};
   long best_cost = -1;
   for (int G = 1; G <= std::min(gmax, ux); ++G)
     for (int KS = 1; KS <= 8; KS *= 2) {
       if (KS > 1 && (!allow_split || K % (KS * 256) != 0)) continue;
       const long tiles = (long)((ux + G - 1) / G) * KS * m_tiles;
-      const long cost = ((tiles + wpx - 1) / wpx) * (G + 2) * (8 / KS);
+      const long per_worker = (tiles + wpx - 1) / wpx, active = std::min<long>(tiles, wpx);
+      const long kc = K / KS, rounds = (kc + 255) / 256;
+      const long inflight_kb = (long)(depth - 1) * G * nb * 8;
+      long rate = inflight_kb * 1000 / (shared ? 2500 : 3800);
+      rate = std::min(rate, shared ? 45L : 30L);
+      rate = std::min(rate, 700L * std::min(m_tiles, wpx) / active);
+      rate = std::max(rate, 1L);
+      const long tile_kb = (long)G * nb * kc / 32;
+      const long tile_ns = tile_kb * 1000 / rate + rounds * mt_blocks * 100 + (KS > 1 ? 3000 + 200 * KS : 1000);
+      long cost = per_worker * tile_ns;
+      if (tiles % wpx != 0) cost += cost / 10;   // idle or unequally loaded workers: measured worse than the rates above say
       if (best_cost < 0 || cost < best_cost || (cost == best_cost && (G > best.G || (G == best.G && KS < best.KS)))) {
         best_cost = cost; best.G = G; best.KS = KS;
       }

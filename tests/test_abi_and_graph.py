@@ -208,13 +208,25 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
             ux, tiles_m = -(-U // xpm), 1
         else:
             ux, tiles_m = -(-U // n_xcd), mt
+        # cost of the busiest worker, in ns: a tile streams at the rate its bytes in flight allow
+        # (depth - 1 rounds of G * nb blocks of 8 KB over 3.8 us, 2.5 us where m-tiles share the
+        # weights), capped per CU (30 / 45 KB/us) and by the XCD's share of the memory (700 KB/us);
+        # 0.1 us per round and 16-row block; 1 us per tile, 3 us + 0.2 us per slice per split-K tile
+        depth = 3 if blocks >= 4 or (blocks == 2 and nb == 1) else 4
+        shared = tiles_m > 1
         best = None
         for G in range(1, min(gmax, max(1, ux)) + 1):
             for KS in (1, 2, 4, 8):
                 if KS > 1 and (not split_ok or K % (KS * 256)):
                     continue
                 tiles = -(-ux // G) * KS * tiles_m
-                cost = -(-tiles // wpx) * (G + 2) * (8 // KS)
+                kc = K // KS
+                rate = (depth - 1) * G * nb * 8 * 1000 // (2500 if shared else 3800)
+                rate = max(1, min(rate, 45 if shared else 30, 700 * min(tiles_m, wpx) // min(tiles, wpx)))
+                tile_ns = G * nb * kc // 32 * 1000 // rate + -(-kc // 256) * blocks * 100 + (3000 + 200 * KS if KS > 1 else 1000)
+                cost = -(-tiles // wpx) * tile_ns
+                if tiles % wpx:
+                    cost += cost // 10      # idle or unequally loaded workers
                 if best is None or (cost, -G, KS) < best[0]:
                     best = ((cost, -G, KS), G, KS)
         return best[1] << 12 | best[2] << 16
