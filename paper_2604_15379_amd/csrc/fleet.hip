@@ -15,6 +15,16 @@
 #include "../../include/fleet.h"
 #include "graph.hpp"
 #include "kernels.hip.inc"
+#include "aux_kernels.hip.inc"
+
+// The flavours of the persistent kernel are instantiated in translation units of their own
+// (kernel_variant.hip, one per flavour, compiled in parallel); here only their addresses are used.
+#define FLEET_EXTERN_VARIANT(V)                                                        \
+  extern template __global__ void fleet_persistent_kernel<V, false>(dev::Params);     \
+  extern template __global__ void fleet_persistent_kernel<V, true>(dev::Params);
+FLEET_EXTERN_VARIANT(0) FLEET_EXTERN_VARIANT(1) FLEET_EXTERN_VARIANT(2) FLEET_EXTERN_VARIANT(3)
+FLEET_EXTERN_VARIANT(4) FLEET_EXTERN_VARIANT(5) FLEET_EXTERN_VARIANT(6)
+#undef FLEET_EXTERN_VARIANT
 
 // Workspace of fleet_decode_step_static, the entry point that allocates nothing: the
 // activations, partial sums, counters and status block of one step live in this array
