@@ -474,6 +474,35 @@ int run_layers(fleet* f, const StepArgs& a, hipStream_t st) {
   return launch(P, dg, f->info.n_cu, preset, st);
 }
 
+// Launch every kernel flavour the fleet's graphs use once, on empty queues (the workers start
+// up, find nothing to do and leave): the runtime's own set-up for a kernel -- scratch memory for
+// spilled registers above all -- then happens in fleet_create, not in the first step that needs it.
+int warm_kernels(fleet* f) {
+  bool seen[dev::N_VARIANTS] = {false};
+  for (auto& dgp : f->graphs) {
+    DevGraph* dg = dgp.get();
+    const int v = variant_for(dg->g.header[H_PATH], dg->g.header[H_BATCH], dg->g.header[H_TILE_M]);
+    if (seen[v]) continue;
+    seen[v] = true;
+    Work w;
+    work_layout(f, dg, f->work, &w);
+    for (int paged = 0; paged < 2; ++paged) {
+      dev::Params P;
+      memset(&P, 0, sizeof(P));
+      fill_graph_params(P, dg);
+      P.n_events = 0;   // no event table to cache, no task to run
+      P.ctr = w.ctr; P.status = w.status;
+      P.n_iter = 1; P.n_xcd = f->info.n_xcd; P.flags = f->shape.flags & ~(FLEET_FLAG_TRACE | FLEET_FLAG_TIMING);
+      P.timeout_ticks = f->timeout_ticks; P.batch = 1; P.hidden = f->shape.hidden;
+      P.page_size = paged ? 64 : 0; P.n_pages = paged;
+      int rc = launch(P, dg, f->info.n_cu, -1, nullptr);
+      if (rc) return rc;
+    }
+  }
+  HIP_TRY(hipDeviceSynchronize());
+  return FLEET_OK;
+}
+
 int check_step_args(const fleet* f, int batch, const void* hidden_in, const int32_t* tokens, const void* kc, const void* vc,
                     const int32_t* positions, const float* hidden_out) {
   if (!f || batch < 1 || batch > f->shape.max_batch || !kc || !vc || !positions || !hidden_out) return FLEET_EINVAL;
@@ -569,6 +598,7 @@ int fleet_create(const fleet_shape_t* shape, const fleet_weights_t* w, fleet_t**
       (loop ? f->graphs_loop : f->graphs).push_back(std::move(dg));
     }
   if ((rc = upload(&f->work, nullptr, f->work_bytes))) return rc;
+  if ((rc = warm_kernels(f.get()))) return rc;
   {   // a status block that reads "ok" before the first step
     Work w0;
     work_layout(f.get(), f->graphs[0].get(), f->work, &w0);
