@@ -356,7 +356,7 @@ int upload_graph(DevGraph* dg, const fleet* f, const void* const* gemm_copies, i
   for (int x = 0; x < n_xcd; ++x)
     for (int qi = g.qoff[x]; qi < g.qoff[x + 1]; ++qi) {
       const int32_t* e = &g.qents[(size_t)qi * QENT_WORDS];
-      if (e[Q_DIST] != D_XCD_RR) continue;
+      if (e[Q_DIST] != D_XCD_RR && e[Q_DIST] != D_XCD_RR_TOP) continue;
       for (int t = e[Q_FIRST]; t < e[Q_FIRST] + e[Q_COUNT]; ++t) fat[(size_t)t * dev::FAT_WORDS + dev::FAT_GROUP] = e[Q_COUNT];
     }
   if ((rc = upload(&dg->fat, fat.data(), fat.size() * 4))) return rc;

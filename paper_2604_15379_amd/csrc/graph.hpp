@@ -39,7 +39,10 @@ enum Body { B_INGEST = 0, B_RMSNORM = 1, B_GEMM = 2, B_ATTN = 3, B_SWIGLU = 4, B
 enum Epi { E_STORE_F32 = 0, E_RESID_F32 = 1, E_SWIGLU_BF16 = 2 };
 enum Path { P_FMA = 0, P_MFMA = 1 };
 enum Scope { S_WAVE = 0, S_CU = 1, S_CHIPLET = 2 };
-enum Dist { D_CHIPLET = 0, D_XCD_RR = 1, D_DEV_RR = 2 };
+// how a queue entry's tasks reach the workers: every worker of the XCD runs the (one) task;
+// dealt round-robin over the XCD's workers from rank 0 up, or (D_XCD_RR_TOP) from the highest
+// rank down; dealt over all workers of the device
+enum Dist { D_CHIPLET = 0, D_XCD_RR = 1, D_DEV_RR = 2, D_XCD_RR_TOP = 3 };
 // EV_TWO_LEVEL: signalled by the workers of chiplet-tasks; EV_TWO_LEVEL_CU: by CU-tasks
 // grouped per XCD (cooperative schedule); EV_DIRECT: by CU-tasks running anywhere
 enum EventKind { EV_DIRECT = 0, EV_TWO_LEVEL = 1, EV_TWO_LEVEL_CU = 2 };

@@ -161,7 +161,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
         tasks.append([o, scope, xcd, *a, wait, sig, stage[0]] + [0] * 6)
         return len(tasks) - 1
 
-    def cu_stage(o, items, wait, min_per_xcd=1):
+    def cu_stage(o, items, wait, min_per_xcd=1, from_top=False):
         ev = len(events)
         if sched == 1 or len(items) <= min_per_xcd * n_xcd:   # tasks run anywhere, or few per XCD: every
             events.append([len(items), 0, 0, len(items)])   # task signals the device counter
@@ -178,7 +178,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
             for x in range(n_xcd):
                 mine = [a for key, a in items if key % n_xcd == x]
                 if mine:
-                    queues[x].append([len(tasks), len(mine), 1, stage[0]])
+                    queues[x].append([len(tasks), len(mine), 3 if from_top else 1, stage[0]])   # 3: dealt from the highest rank down
                     for a in mine:
                         task(o, 1, x, a, wait, ev)
         stage[0] += 1
@@ -297,7 +297,8 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
             o_qkv = op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["X"], BUF["QKV"], 0, WK["QKV"],
                        WK["LN1"] | 2 << 8 | PRE)
         else:
-            ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN1"]), rows, ev)
+            ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN1"]), rows, ev, 1,
+                          batch <= 4 * n_xcd)     # few norm tasks per XCD: on its highest ranks
             o_qkv = op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["N"], BUF["QKV"], 0, WK["QKV"],
                        xm(H) | plan(NQKV // ur, H, 1))
         ev = gemm_stage(o_qkv, ev)
