@@ -269,11 +269,12 @@ int resolve_tile_m(int batch, int tile_m, int fma_max) {
 }
 
 int attention_splits(int batch, int n_kv_heads, int n_workers, int max_seq) {
-  // as many splits as there are idle workers, but no split shorter than 128 cache slots
+  // as many splits as there are idle workers, but no split shorter than about 100 cache slots
+  // (measured at batch 1: a capacity of 1001 slots runs 2 % faster with 8 splits than with 4, 1025 slots 7 % slower with 16 than with 8)
   // (a split costs a fixed prologue and its partial has to be merged)
   int pairs = std::max(1, batch * n_kv_heads);
   int s = 1;
-  while (s * 2 <= 32 && pairs * s * 2 <= n_workers && s * 2 * 128 <= max_seq) s *= 2;
+  while (s * 2 <= 32 && pairs * s * 2 <= n_workers && s * 2 * 100 <= max_seq) s *= 2;
   return s;
 }
 

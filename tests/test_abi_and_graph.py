@@ -147,7 +147,7 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
     tm = batch if fma else (tile_m or min(64, -(-batch // 16) * 16))
     mt = -(-batch // tm)
     S = 1
-    while S * 2 <= 32 and batch * nkv * S * 2 <= n_workers and S * 2 * 128 <= sh.max_seq:
+    while S * 2 <= 32 and batch * nkv * S * 2 <= n_workers and S * 2 * 100 <= sh.max_seq:
         S *= 2
     ops, tasks, events, queues, marks, xready = [], [], [], [[] for _ in range(n_xcd)], [], []
     stage = [0]
