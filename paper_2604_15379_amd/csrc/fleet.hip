@@ -51,6 +51,7 @@ struct DevInfo {
 struct Work {
   float* x = nullptr; void* n = nullptr; float* qkv = nullptr; void* att = nullptr; void* h = nullptr;
   float* part = nullptr; float* gpart = nullptr; float* gu32 = nullptr;
+  float* ss = nullptr;       // sums of squares of the residual rows, per 16 features
   uint32_t* ctr = nullptr; int32_t* status = nullptr;
   size_t gpart_region = 0;   // bytes between the per-XCD regions of gpart
 };
@@ -275,11 +276,12 @@ size_t work_layout(const fleet* f, const DevGraph* dg, char* base, Work* w) {
   char* part = take(B * s.n_kv_heads * S * grp * dev::PART_STRIDE * 4);
   char* gpart = take(gp * regions);
   char* gu32 = take((s.flags & FLEET_FLAG_UNFUSED_SILU) ? B * 2 * F * 4 : 0);
+  char* ss = take(B * (H / 16) * 4);
   char* ctr = take((size_t)dg->ctr_words * 4);
   char* status = take(dev::ST_WORDS * 4);
   if (w) {
     w->x = (float*)x; w->n = n; w->qkv = (float*)qkv; w->att = att; w->h = h; w->part = (float*)part;
-    w->gpart = (float*)gpart; w->gu32 = (float*)gu32; w->ctr = (uint32_t*)ctr; w->status = (int32_t*)status;
+    w->gpart = (float*)gpart; w->gu32 = (float*)gu32; w->ss = (float*)ss; w->ctr = (uint32_t*)ctr; w->status = (int32_t*)status;
     w->gpart_region = gp;
   }
   return off;
@@ -443,7 +445,7 @@ int run_layers(fleet* f, const StepArgs& a, hipStream_t st) {
   fill_graph_params(P, dg);
   P.ctr = w.ctr; P.status = w.status;
   P.buf[BUF_X] = w.x; P.buf[BUF_N] = w.n; P.buf[BUF_QKV] = w.qkv; P.buf[BUF_ATT] = w.att; P.buf[BUF_H] = w.h;
-  P.buf[BUF_PART] = w.part; P.buf[BUF_GPART] = w.gpart; P.buf[BUF_GU32] = w.gu32;
+  P.buf[BUF_PART] = w.part; P.buf[BUF_GPART] = w.gpart; P.buf[BUF_GU32] = w.gu32; P.buf[BUF_SS] = w.ss;
   P.buf[BUF_HIDDEN_IN] = (void*)a.hidden_in; P.buf[BUF_TOKENS] = (void*)a.tokens;
   P.buf[BUF_KC] = a.k_cache; P.buf[BUF_VC] = a.v_cache; P.buf[BUF_POS] = (void*)a.positions;
   P.buf[BUF_HIDDEN_OUT] = a.hidden_out; P.buf[BUF_LOGITS] = a.logits; P.buf[BUF_TOKENS_OUT] = a.tokens_out;
@@ -467,7 +469,11 @@ int run_layers(fleet* f, const StepArgs& a, hipStream_t st) {
     P.q_begin[x] = g.marks[(size_t)x * nm + mb];
     P.q_end[x] = g.marks[(size_t)x * nm + me];
   }
-  if (a.x_in) HIP_TRY(hipMemcpyAsync(w.x, a.x_in, (size_t)a.batch * f->shape.hidden * 4, hipMemcpyDeviceToDevice, st));
+  if (a.x_in) {   // a residual stream from the caller: copy it in, with the sums of squares its first consumer needs
+    HIP_TRY(hipMemcpyAsync(w.x, a.x_in, (size_t)a.batch * f->shape.hidden * 4, hipMemcpyDeviceToDevice, st));
+    hipLaunchKernelGGL(fleet_row_ss_kernel, dim3(std::max(1, a.batch * (f->shape.hidden / 16) / 256)), dim3(256), 0, st,
+                       (const float*)w.x, w.ss, a.batch, f->shape.hidden);
+  }
   const int preset = a.with_ingest ? -1 : g.xready[a.layer_begin];
   f->last_status = w.status;
   f->last_x = w.x;

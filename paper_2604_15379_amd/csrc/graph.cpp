@@ -330,6 +330,12 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
   // normalises the L2-resident residual rows into LDS); MFMA path: CU-task per row
   const bool fuse_norm = path == P_FMA && !(s.flags & FLEET_FLAG_SEPARATE_NORM) &&
                          (int64_t)batch * H * 2 <= GEMV_LDS_X_BYTES;
+  // MFMA path, tiles of 16 batch rows: fused as well.  The GEMM reads the fp32 residual rows and
+  // scales them into its bf16 operands itself; the sums of squares come from the epilogues that
+  // wrote the rows (one partial per row and 16 features, BUF_SS).  Taller tiles have no
+  // registers left for fp32 operands and keep the norm stages.
+  const bool fuse_norm_mfma = path == P_MFMA && !(s.flags & FLEET_FLAG_SEPARATE_NORM) &&
+                              mfma_blocks(tm) <= FUSED_NORM_MAX_BLOCKS && H % 64 == 0 && H <= 32768;
   auto xmode = [&](int K) { return path == P_FMA && (int64_t)batch * K * 2 <= GEMV_LDS_X_BYTES ? X_LDS_COPY : X_GLOBAL; };
   // weight blocks requested before the wait (bits 10..11 of aux2).  Measured at batch 1:
   // requesting only one block after the short O-projection stage (to reach the poll
@@ -355,6 +361,9 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
     if (fuse_norm) {
       op_qkv = b.add_op(B_GEMM, l, E_STORE_F32, path, H, NQKV, ur, NQKV / ur, mt, tm, BUF_X, BUF_QKV, 0, W_QKV,
                         W_LN1 | (X_LDS_NORM << 8) | PRE2);   // FMA path only
+    } else if (fuse_norm_mfma) {
+      op_qkv = b.add_op(B_GEMM, l, E_STORE_F32, path, H, NQKV, ur, NQKV / ur, mt, tm, BUF_X, BUF_QKV, 0, W_QKV,
+                        W_LN1 | PRE2 | AUX2_FUSED_NORM | plan_bits(NQKV / ur, H, 1));
     } else {
       // the norm tasks go to the XCD's highest ranks: where the QKV weights stay in registers the
       // lowest ranks hold the tiles and request their whole share before the wait -- a worker
@@ -399,6 +408,9 @@ Graph build_decode_graph(const fleet_shape_t& s, int batch, int n_xcd, int n_wor
     if (fuse_norm) {
       op_gu = b.add_op(B_GEMM, l, gu_epi, path, H, gu_n, ur, gu_n / ur, mt, tm, BUF_X, gu_out, gu_aux, W_GU,
                        W_LN2 | (X_LDS_NORM << 8) | PRE2);
+    } else if (fuse_norm_mfma) {
+      op_gu = b.add_op(B_GEMM, l, gu_epi, path, H, gu_n, ur, gu_n / ur, mt, tm, BUF_X, gu_out, gu_aux, W_GU,
+                       W_LN2 | PRE2 | AUX2_FUSED_NORM | plan_bits(gu_n / ur, H, gu_nb));
     } else {
       int op_n2 = b.add_op(B_RMSNORM, l, E_STORE_F32, P_FMA, H, H, 0, 0, 1, batch, BUF_X, BUF_N, 0, W_LN2);
       ev = b.cu_stage(op_n2, batch, ev, row_key, row_arg);

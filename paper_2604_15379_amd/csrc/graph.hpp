@@ -54,7 +54,9 @@ constexpr int ATTN_TWO_LEVEL_MIN_PER_XCD = 32;
 // activation / caller buffers, resolved to pointers per step
 enum Buf {
   BUF_NONE = 0, BUF_X, BUF_N, BUF_QKV, BUF_ATT, BUF_H, BUF_PART, BUF_HIDDEN_IN, BUF_TOKENS,
-  BUF_KC, BUF_VC, BUF_POS, BUF_HIDDEN_OUT, BUF_LOGITS, BUF_GEMM_X, BUF_GEMM_Y, BUF_GPART, BUF_GU32, BUF_TOKENS_OUT, BUF_PT, N_BUF
+  BUF_KC, BUF_VC, BUF_POS, BUF_HIDDEN_OUT, BUF_LOGITS, BUF_GEMM_X, BUF_GEMM_Y, BUF_GPART, BUF_GU32, BUF_TOKENS_OUT, BUF_PT,
+  BUF_SS,   // fp32 [batch][hidden / 16]: sums of squares of the residual stream, one per row and 16 features
+  N_BUF
 };
 
 // which caller weight an op reads (resolved with the op's layer)
@@ -74,7 +76,10 @@ enum {
 // path requests before its dependency wait (0..3); MFMA path: bits 12..15 = units per tile,
 // bits 16..19 = k-slices of the split-K plan (1 = no split), bit 20 = counter set of the
 // split-K arrival counters (isolated GEMM repetitions alternate), bit 21 = register-resident
-// weights (MfmaPlan::resident)
+// weights (MfmaPlan::resident), bit 22 = the op reads the fp32 residual stream and normalises
+// it itself (RMSNorm fused into the MFMA GEMM; the gain is the op's second pointer)
+constexpr int AUX2_FUSED_NORM = 1 << 22;
+constexpr int FUSED_NORM_MAX_BLOCKS = 1;   // tallest tile (in blocks of 16 batch rows) whose kernel flavour has the fused norm
 enum XMode { X_GLOBAL = 0, X_LDS_COPY = 1, X_LDS_NORM = 2 };
 constexpr int GEMV_LDS_X_BYTES = 96 * 1024;   // LDS the FMA path may fill with activations
 // task word indices.  A0..A3 by body:

@@ -130,7 +130,7 @@ def test_step_bytes_accounting():
 
 # ------------------------------------------------------------------ graph re-derivation
 BUF = dict(NONE=0, X=1, N=2, QKV=3, ATT=4, H=5, PART=6, HIDDEN_IN=7, TOKENS=8, KC=9, VC=10, POS=11,
-           HIDDEN_OUT=12, LOGITS=13, GEMM_X=14, GEMM_Y=15, GPART=16, GU32=17)
+           HIDDEN_OUT=12, LOGITS=13, GEMM_X=14, GEMM_Y=15, GPART=16, GU32=17, TOKENS_OUT=18, PT=19, SS=20)
 WK = dict(NONE=0, QKV=1, O=2, GU=3, DOWN=4, LM=5, LN1=6, LN2=7, FINAL=8, EMBED=9)
 INGEST, RMSNORM, GEMM, ATTN, SWIGLU, FINAL = 0, 1, 2, 3, 4, 5
 LDS_X_BYTES = 96 * 1024      # activations the FMA path may keep in LDS
@@ -277,6 +277,10 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
     # FMA path: RMSNorm fused into the consuming GEMV (activation mode 2, gain kind in the
     # low byte of aux2); activations that fit LDS are copied there (mode 1), else mode 0
     fuse = fma and not (flags & 4) and batch * H * 2 <= LDS_X_BYTES
+    # MFMA path, tiles of 16 rows: fused too (bit 22 of aux2; the GEMM reads the fp32 residual
+    # rows); taller tiles keep the norm stages
+    fuse_mfma = (not fma) and not (flags & 4) and tm <= 16 and H % 64 == 0 and H <= 32768
+    FUSED = 1 << 22
 
     PRE = 3 << 10     # weight blocks the FMA path requests before its wait (bits 10..11)
 
@@ -296,6 +300,9 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
         if fuse:
             o_qkv = op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["X"], BUF["QKV"], 0, WK["QKV"],
                        WK["LN1"] | 2 << 8 | PRE)
+        elif fuse_mfma:
+            o_qkv = op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["X"], BUF["QKV"], 0, WK["QKV"],
+                       WK["LN1"] | PRE | FUSED | plan(NQKV // ur, H, 1))
         else:
             ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN1"]), rows, ev, 1,
                           batch <= 4 * n_xcd)     # few norm tasks per XCD: on its highest ranks
@@ -319,6 +326,9 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
         if fuse:
             o_gu = op(GEMM, l, epi, path, H, gn, ur, gn // ur, mt, tm, BUF["X"], gout, gaux, WK["GU"],
                       WK["LN2"] | 2 << 8 | PRE)
+        elif fuse_mfma:
+            o_gu = op(GEMM, l, epi, path, H, gn, ur, gn // ur, mt, tm, BUF["X"], gout, gaux, WK["GU"],
+                      WK["LN2"] | PRE | FUSED | plan(gn // ur, H, gnb))
         else:
             ev = cu_stage(op(RMSNORM, l, 0, 0, H, H, 0, 0, 1, batch, BUF["X"], BUF["N"], 0, WK["LN2"]), rows, ev)
             o_gu = op(GEMM, l, epi, path, H, gn, ur, gn // ur, mt, tm, BUF["N"], gout, gaux, WK["GU"],

@@ -81,6 +81,32 @@ def test_schedules_agree_with_oracle(batch, sched, tile_m, flags):
     check_new_kv(m, got[2], got[3], k, v)
 
 
+@pytest.mark.parametrize("batch", [2, 3])          # FMA-path kernel, MFMA-path kernel (split-K tiles as CU-tasks)
+def test_first_steps_of_fresh_fleets_unaware_split_kv(batch):
+    """Chiplet-unaware schedule with two KV splits per (sequence, kv head): the splits of a pair run
+    on different XCDs, and so do the k-slices of a split-K tile, so their partial sums cross XCDs.
+    Those were once stored into the writer's L2 and written back by one thread after the
+    workgroup's barrier, which lost another wavefront's acknowledged stores about once in a
+    thousand steps (one whole output row wrong); they are written through now.  The first step
+    of many fresh fleets must give the same bits every time."""
+    print(f"fresh fleets, unaware schedule, batch={batch}", flush=True)
+    sh = si.reduced_shape(max_batch=batch, max_seq=200, n_layers=2, vocab=1024)
+    pos = np.random.default_rng(7).integers(1, 200, batch).astype(np.int32)
+    m = Model(sh, seed=3, batch=batch, positions=pos)
+    g = F.parse_graph(F.fleet_graph_build(sh.asdict(), batch, 8, 256, 1, 16, 0))
+    assert g["header"]["n_splits"] == 2
+    first = None
+    for it in range(300):
+        got = m.run_gpu(1, 16, 0)
+        if first is None:
+            first = got
+            (ho, lg), _, _ = m.run_oracle()
+            assert_close(got[0], ho, "hidden_out")
+            assert_close(got[1], lg, "logits")
+        else:
+            assert np.array_equal(got[0], first[0]) and np.array_equal(got[1], first[1]), f"step of fleet {it} differs"
+
+
 @pytest.mark.parametrize("batch", [1, 3])          # FMA-path kernel, MFMA-path kernel
 @pytest.mark.parametrize("ramp", ["up", "down", "wave"])
 def test_attention_scores_of_wide_range(batch, ramp):
