@@ -92,7 +92,7 @@ typedef struct {
   int32_t tile_m;     /* GEMM tile height along the batch on the MFMA path: 16, 32, 64, or
                          0 = whole batch rounded up to 16 (reads each weight once).
                          Batches above 64 use 64-row tiles (0) or the given height.
-                         Batches up to 2 run FMA GEMV kernels, larger ones bf16 MFMA
+                         Batch 1 runs FMA GEMV kernels, larger batches bf16 MFMA
                          kernels; the environment variable FLEET_FMA_MAX_BATCH (0..8),
                          read once by fleet_create (and by fleet_gemm and
                          fleet_graph_build per call), moves that switch                 */

@@ -252,13 +252,13 @@ static MfmaPlan plan_for(int sched, int flags, int n_units, int K, int nb, int t
   return plan_mfma((n_units + n_xcd - 1) / std::max(1, n_xcd), wpx, K, nb, mfma_blocks(tile_m), m_tiles, split_ok);
 }
 
-// Largest batch that runs the FMA GEMV kernels.  Measured on MI355X the MFMA kernels win from
-// batch 3 on (per step: batch 2 3.77 ms with either, batch 3 4.41 ms FMA / 3.80 ms MFMA, batch 4
-// 4.58 / 3.78), so the default is 2; the environment variable FLEET_FMA_MAX_BATCH (0..8) moves
-// the switch, e.g. to 8 for FMA at batch 3-8.
+// Largest batch that runs the FMA GEMV kernels.  Measured on MI355X the MFMA kernels (with the
+// RMSNorm fused into them) win from batch 2 on (12 layers, per step: batch 1 0.984 ms FMA / 1.080
+// ms MFMA, batch 2 1.147 / 1.104), so the default is 1; the environment variable
+// FLEET_FMA_MAX_BATCH (0..8) moves the switch, e.g. to 8 for FMA at batch 2-8.
 int fma_max_from_env() {
   const char* e = getenv("FLEET_FMA_MAX_BATCH");
-  if (!e) return 2;
+  if (!e) return 1;
   return std::min(8, std::max(0, atoi(e)));
 }
 

@@ -115,7 +115,7 @@ struct MfmaPlan { int G, KS, resident; };
 MfmaPlan plan_mfma(int units_per_xcd, int workers_per_xcd, int K, int nb, int mt_blocks, int m_tiles, bool allow_split);
 // 16-row blocks of batch rows the MFMA kernel for tile height tile_m accumulates (1, 2 or 4)
 int mfma_blocks(int tile_m);
-// largest batch that runs the FMA GEMV kernels (larger batches run the MFMA kernels): 2, or
+// largest batch that runs the FMA GEMV kernels (larger batches run the MFMA kernels): 1, or
 // what the environment variable FLEET_FMA_MAX_BATCH (0..8) says.  Read once by whoever owns
 // a set of graphs (fleet_create, fleet_gemm, fleet_graph_build) and handed to the builders, so
 // that the graphs and the packed weight copies of one owner always agree.

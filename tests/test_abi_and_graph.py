@@ -72,7 +72,7 @@ def test_fma_switch_follows_the_environment_of_the_builder(monkeypatch):
     call) and handed to the builder; FLEET_FLAG_PACKED_ONLY forces the MFMA path for every batch."""
     sh = si.reduced_shape(max_batch=8).asdict()
     path = lambda b, flags=0: F.parse_graph(F.fleet_graph_build(sh, b, flags=flags))["header"]["path"]
-    assert [path(b) for b in (1, 2, 3, 8)] == [0, 0, 1, 1]
+    assert [path(b) for b in (1, 2, 3, 8)] == [0, 1, 1, 1]
     monkeypatch.setenv("FLEET_FMA_MAX_BATCH", "8")
     assert [path(b) for b in (1, 2, 3, 8)] == [0, 0, 0, 0]
     assert [path(b, F.FLAG_PACKED_ONLY) for b in (1, 8)] == [1, 1]
@@ -136,7 +136,7 @@ INGEST, RMSNORM, GEMM, ATTN, SWIGLU, FINAL = 0, 1, 2, 3, 4, 5
 LDS_X_BYTES = 96 * 1024      # activations the FMA path may keep in LDS
 
 
-FMA_MAX = 2   # largest batch on the FMA GEMV path (FLEET_FMA_MAX_BATCH unset)
+FMA_MAX = 1   # largest batch on the FMA GEMV path (FLEET_FMA_MAX_BATCH unset)
 
 
 def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0):

@@ -39,7 +39,7 @@ def test_two_layers_ragged_positions_with_lm_head(batch):
     check_new_kv(m, got[2], got[3], k, v)
 
 
-@pytest.mark.parametrize("batch,fma_max", [(5, 8), (8, 8), (4, 4), (3, 4), (2, 1), (1, 0)])
+@pytest.mark.parametrize("batch,fma_max", [(5, 8), (8, 8), (4, 4), (3, 4), (2, 2), (2, 1), (1, 0)])
 def test_fma_mfma_switch_moved_by_environment(monkeypatch, batch, fma_max):
     """FLEET_FMA_MAX_BATCH moves the batch at which the GEMMs switch from the FMA GEMV kernels
     to the MFMA kernels: batch 3 to 8 on the FMA kernels, batch 1 and 2 on the MFMA ones."""
@@ -68,7 +68,7 @@ def test_fma_mfma_switch_moved_by_environment(monkeypatch, batch, fma_max):
                                                  (1, 0, F.FLAG_NO_RESIDENT), (0, 0, F.FLAG_UNFUSED_SILU),
                                                  (1, 16, F.FLAG_UNFUSED_SILU), (0, 0, F.FLAG_NT_STORES),
                                                  (1, 16, F.FLAG_NT_STORES)])
-@pytest.mark.parametrize("batch", [2, 3, 40])      # FMA path, MFMA path with one and with three 16-row blocks
+@pytest.mark.parametrize("batch", [1, 3, 40])      # FMA path, MFMA path with one and with three 16-row blocks
 def test_schedules_agree_with_oracle(batch, sched, tile_m, flags):
     print(f"decode modes batch={batch} sched={sched} tile_m={tile_m} flags={flags}", flush=True)
     sh = si.reduced_shape(max_batch=batch, max_seq=200, n_layers=2, vocab=1024)
@@ -81,14 +81,15 @@ def test_schedules_agree_with_oracle(batch, sched, tile_m, flags):
     check_new_kv(m, got[2], got[3], k, v)
 
 
-@pytest.mark.parametrize("batch", [2, 3])          # FMA-path kernel, MFMA-path kernel (split-K tiles as CU-tasks)
-def test_first_steps_of_fresh_fleets_unaware_split_kv(batch):
+@pytest.mark.parametrize("batch,fma_max", [(2, 2), (3, 1)])   # FMA-path kernel, MFMA-path kernel (split-K tiles as CU-tasks)
+def test_first_steps_of_fresh_fleets_unaware_split_kv(monkeypatch, batch, fma_max):
     """Chiplet-unaware schedule with two KV splits per (sequence, kv head): the splits of a pair run
     on different XCDs, and so do the k-slices of a split-K tile, so their partial sums cross XCDs.
     Those were once stored into the writer's L2 and written back by one thread after the
     workgroup's barrier, which lost another wavefront's acknowledged stores about once in a
     thousand steps (one whole output row wrong); they are written through now.  The first step
     of many fresh fleets must give the same bits every time."""
+    monkeypatch.setenv("FLEET_FMA_MAX_BATCH", str(fma_max))
     print(f"fresh fleets, unaware schedule, batch={batch}", flush=True)
     sh = si.reduced_shape(max_batch=batch, max_seq=200, n_layers=2, vocab=1024)
     pos = np.random.default_rng(7).integers(1, 200, batch).astype(np.int32)

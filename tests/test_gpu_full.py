@@ -160,7 +160,8 @@ def test_batch64_kv4096_cooperative_and_unaware(weights):
 @pytest.mark.parametrize("batch,sched,tile_m,fma_max", [
     (32, F.SCHED_UNAWARE, 0, None),      # chiplet-unaware schedule with the whole-batch tile
     (32, F.SCHED_MSPLIT, 16, None),      # M-split over 16-row tiles
-    (2, F.SCHED_COOPERATIVE, 0, None),   # FMA GEMV kernel with two batch rows
+    (2, F.SCHED_COOPERATIVE, 0, 2),      # FMA GEMV kernel with two batch rows
+    (2, F.SCHED_COOPERATIVE, 0, None),   # MFMA kernel, two rows of a 16-row block
     (16, F.SCHED_COOPERATIVE, 0, None),  # MFMA kernel, one full 16-row block
     (8, F.SCHED_COOPERATIVE, 0, 8),      # FMA GEMV kernel with eight batch rows
     (4, F.SCHED_COOPERATIVE, 0, 8),      # FMA GEMV kernel with four batch rows
