@@ -27,23 +27,23 @@ HBM_PEAK_GBPS = 8000.0
 # same counters read for a plain copy of known size.  Key: (batch, kv, kv_min, sched, tile_m, flags)
 # at 36 layers and seed 2; any other workload reports null unless --traffic-bytes is given.
 MEASURED_TRAFFIC = {
-    (1, 1024, 0, 0, 0, 0): 15435725312,
-    (1, 1024, 0, 1, 0, 0): 15431531424,
-    (1, 1024, 0, 0, 0, 64): 16178037248,
-    (1, 1024, 0, 0, 0, 256): 16257064128,
-    (8, 2048, 1024, 0, 0, 0): 17327438784,
-    (8, 2048, 1024, 0, 0, 4): 17340947328,
-    (8, 2048, 1024, 1, 0, 0): 17488165152,
-    (32, 2048, 1024, 0, 0, 0): 23731294976,
-    (32, 2048, 1024, 0, 16, 0): 24141662144,
-    (32, 2048, 1024, 1, 16, 0): 32714612160,
-    (32, 2048, 1024, 2, 16, 0): 38876165120,
-    (64, 4096, 0, 0, 0, 0): 55957942080,
-    (64, 4096, 0, 0, 16, 0): 57063732800,
-    (64, 4096, 0, 1, 16, 0): 81744576320,
-    (64, 4096, 0, 2, 16, 0): 100613699328,
-    (64, 4096, 0, 0, 16, 32): 56758067776,
-    (64, 4096, 0, 0, 16, 2048): 57064407808,
+    (1, 1024, 0, 0, 0, 0): 15436541376,
+    (1, 1024, 0, 1, 0, 0): 15431131552,
+    (1, 1024, 0, 0, 0, 64): 16204215872,
+    (1, 1024, 0, 0, 0, 256): 16261093312,
+    (8, 2048, 1024, 0, 0, 0): 17321967040,
+    (8, 2048, 1024, 0, 0, 4): 17341185344,
+    (8, 2048, 1024, 1, 0, 0): 17483146336,
+    (32, 2048, 1024, 0, 0, 0): 23732238272,
+    (32, 2048, 1024, 0, 16, 0): 24143764288,
+    (32, 2048, 1024, 1, 16, 0): 32709316352,
+    (32, 2048, 1024, 2, 16, 0): 38880241408,
+    (64, 4096, 0, 0, 0, 0): 55953641088,
+    (64, 4096, 0, 0, 16, 0): 57067202496,
+    (64, 4096, 0, 1, 16, 0): 81740070144,
+    (64, 4096, 0, 2, 16, 0): 100611870784,
+    (64, 4096, 0, 0, 16, 32): 56761924928,
+    (64, 4096, 0, 0, 16, 2048): 57060511104,
 }
 
 
