@@ -361,6 +361,73 @@ def test_decode_step_matches_torch_library_composition():
     assert np.abs(ho3 - ho2).max() <= 2e-2 * np.sqrt(np.mean(rx ** 2))
 
 
+def _torch_step_rounded(sh, w, hid, kc, vc, pos, drop=None):
+    """The fp64 torch composition with values rounded to bf16 wherever a tensor crosses an
+    operator boundary (paper section 2.2, the operators of a layer): the three norm outputs, q and
+    k after head norm and rotation, v, the attention output, the SwiGLU product.  drop names
+    one of those points to leave unrounded."""
+    f64 = lambda t: t.to(torch.float64)
+    rb = lambda t: t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+    R = lambda name, t: t if drop == name else rb(t)
+    B = hid.shape[0]
+    hd, nq, nkv = sh.head_dim, sh.n_q_heads, sh.n_kv_heads
+    kc, vc = f64(kc).clone(), f64(vc).clone()
+    x = f64(hid)
+    inv = torch.pow(torch.tensor(sh.rope_theta, dtype=torch.float64),
+                    -torch.arange(0, hd, 2, dtype=torch.float64) / hd)
+
+    def rope(t, p):
+        z = torch.complex(t[..., : hd // 2], t[..., hd // 2:]) * \
+            torch.polar(torch.ones_like(inv), p * inv)
+        return torch.cat([z.real, z.imag], -1)
+
+    for l in range(sh.n_layers):
+        n = R("ln1", F.rms_norm(x, (sh.hidden,), f64(w["ln1"][l]), sh.rms_eps))
+        qkv = F.linear(n, f64(w["wqkv"][l]))
+        att = torch.zeros(B, nq * hd, dtype=torch.float64)
+        for b in range(B):
+            p = int(pos[b])
+            q = qkv[b, : nq * hd].view(nq, hd)
+            k = qkv[b, nq * hd: (nq + nkv) * hd].view(nkv, hd)
+            v = qkv[b, (nq + nkv) * hd:].view(nkv, hd)
+            q = R("q", rope(F.rms_norm(q, (hd,), f64(w["q_norm"][l]), sh.rms_eps), p))
+            kc[l, b, :, p] = rb(rope(F.rms_norm(k, (hd,), f64(w["k_norm"][l]), sh.rms_eps), p))
+            vc[l, b, :, p] = rb(v)
+            o = F.scaled_dot_product_attention(q[None, :, None, :], kc[l, b, :, : p + 1][None],
+                                               vc[l, b, :, : p + 1][None], enable_gqa=True)
+            att[b] = o.reshape(-1)
+        x = x + F.linear(R("att", att), f64(w["wo"][l]))
+        n = R("ln2", F.rms_norm(x, (sh.hidden,), f64(w["ln2"][l]), sh.rms_eps))
+        gu = F.linear(n, f64(w["wgu"][l]))
+        x = x + F.linear(R("swiglu", F.silu(gu[:, : sh.ffn]) * gu[:, sh.ffn:]), f64(w["wdown"][l]))
+    nf = R("final", F.rms_norm(x, (sh.hidden,), f64(w["final_norm"]), sh.rms_eps))
+    return x.numpy(), F.linear(nf, f64(w["lm_head"])).numpy(), kc.numpy(), vc.numpy()
+
+
+@pytest.mark.parametrize("seed", [20, 21])
+def test_rounding_points_of_the_decode_step(seed):
+    """Where the oracle rounds to bf16 (its header: every tensor that crosses an operator
+    boundary) is pinned against the fp64 composition rounded at the same points: the two agree
+    to fp32 accumulation error and the new cache entries of every layer are the same bits, while
+    leaving out any single rounding point moves the result a thousand times further."""
+    sh, w, hid, kc, vc, pos = _tiny(seed=seed, n_layers=3)
+    ho, lg, k, v = _run_oracle(sh, w, hid, kc, vc, pos, 0)
+    changed = np.zeros(k.shape[:4], bool)
+    for b in range(len(pos)):
+        changed[:, b, :, pos[b]] = True
+    rms = lambda a: np.sqrt(np.mean(a ** 2))
+    rx, rl, rk, rv = _torch_step_rounded(sh, w, hid, kc, vc, pos)
+    assert np.abs(ho - rx).max() <= 1e-5 * rms(rx)
+    assert np.abs(lg - rl).max() <= 1e-5 * rms(rl)
+    assert np.mean(unbf(k)[changed] == rk[changed]) >= 0.99
+    assert np.mean(unbf(v)[changed] == rv[changed]) >= 0.99
+    for drop in ("ln1", "q", "att", "ln2", "swiglu", "final"):
+        dx, dl, _, _ = _torch_step_rounded(sh, w, hid, kc, vc, pos, drop)
+        assert np.abs(lg - dl).max() >= 1e-3 * rms(rl), drop
+        if drop != "final":
+            assert np.abs(ho - dx).max() >= 1e-3 * rms(rx), drop
+
+
 def test_rows_are_independent_bit_exact():
     sh, w, hid, kc, vc, pos = _tiny(B=3)
     ho, lg, k, v = _run_oracle(sh, w, hid, kc, vc, pos)
