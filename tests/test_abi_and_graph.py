@@ -308,7 +308,9 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
                           batch <= 4 * n_xcd)     # few norm tasks per XCD: on its highest ranks
             o_qkv = op(GEMM, l, 0, path, H, NQKV, ur, NQKV // ur, mt, tm, BUF["N"], BUF["QKV"], 0, WK["QKV"],
                        xm(H) | plan(NQKV // ur, H, 1))
-        ev = gemm_stage(o_qkv, ev)
+        # FMA path: attention workers (at most a quarter of every XCD's workers) sit out QKV too
+        qkv_skip = fma and sched != 1 and all(0 < k and 4 * k <= n_workers // n_xcd for k in o_skip)
+        ev = gemm_stage(o_qkv, ev, o_skip if qkv_skip else None)
         att_items = [(p, [p // nkv, p % nkv, s, S]) for p in range(batch * nkv) for s in range(S)]
         ev = cu_stage(op(ATTN, l, 0, 0, hd, QD, 0, 0, 1, batch, BUF["QKV"], BUF["ATT"], S, WK["NONE"]), att_items, ev, 32)
         # FMA path, cooperative: the O projection carries the gate/up matrix as second pointer
