@@ -193,13 +193,16 @@ int mfma_blocks(int tile_m) { return tile_m <= 16 ? 1 : tile_m <= 32 ? 2 : 4; }
 // XCD's unit slice (ux units, m_tiles m-tiles each, wpx workers), by a cost model fitted to
 // a sweep of plans on MI355X (integer arithmetic; times in ns, sizes in KB, rates in KB/us):
 //   * a worker streams a tile at the rate its bytes in flight allow -- (D - 1) rounds of
-//     G * nb row blocks of 8 KB, over a loaded latency of 3.8 us (2.5 us where several m-tiles
-//     share the weights through the L2) -- capped per CU (30, shared 45) and by the XCD's share
+//     G * nb row blocks of 8 KB, over a loaded latency of 2.5 us -- capped per CU (30, 45
+//     where several m-tiles share the weights through the L2) and by the XCD's share
 //     of the memory bandwidth (700 per XCD over the workers that hold a tile, times the number
 //     of m-tiles that share a weight read);
 //   * a round costs 0.1 us per block of 16 batch rows (activation reads, MFMAs);
 //   * a tile costs 1 us on top (pipeline fill, cross-wave reduction, epilogue), a split-K tile
-//     3 us + 0.2 us per slice (partial sums out, arrival counter, the last arriver's reduction).
+//     3 us + 0.4 us per slice (partial sums out, arrival counter, the last arriver's reduction).
+// (The latency and the cost per slice were refitted inside the decode step: with 3.8 us and
+// 0.2 us, which the isolated sweep suggested, the down projection at batch 17-32 took 8 units
+// x 8 slices where 4 x 4 is 1.4 to 3 % of a step faster.)
 // The worker with the most tiles decides (+10 % where the tiles do not divide evenly among
 // the workers).  Ties: more units per tile, then fewer slices.
 // allow_split = false: one k-slice only.
@@ -217,12 +220,12 @@ MfmaPlan plan_mfma(int ux, int wpx, int K, int nb, int mt_blocks, int m_tiles, b
       const long per_worker = (tiles + wpx - 1) / wpx, active = std::min<long>(tiles, wpx);
       const long kc = K / KS, rounds = (kc + 255) / 256;
       const long inflight_kb = (long)(depth - 1) * G * nb * 8;
-      long rate = inflight_kb * 1000 / (shared ? 2500 : 3800);
+      long rate = inflight_kb * 1000 / 2500;
       rate = std::min(rate, shared ? 45L : 30L);
       rate = std::min(rate, 700L * std::min(m_tiles, wpx) / active);
       rate = std::max(rate, 1L);
       const long tile_kb = (long)G * nb * kc / 32;
-      const long tile_ns = tile_kb * 1000 / rate + rounds * mt_blocks * 100 + (KS > 1 ? 3000 + 200 * KS : 1000);
+      const long tile_ns = tile_kb * 1000 / rate + rounds * mt_blocks * 100 + (KS > 1 ? 3000 + 400 * KS : 1000);
       long cost = per_worker * tile_ns;
       if (tiles % wpx != 0) cost += cost / 10;   // idle or unequally loaded workers: measured worse than the rates above say
       if (best_cost < 0 || cost < best_cost || (cost == best_cost && (G > best.G || (G == best.G && KS < best.KS)))) {

@@ -221,9 +221,9 @@ def expected_graph(sh: si.Shape, batch, n_xcd, n_workers, sched, tile_m, flags=0
                     continue
                 tiles = -(-ux // G) * KS * tiles_m
                 kc = K // KS
-                rate = (depth - 1) * G * nb * 8 * 1000 // (2500 if shared else 3800)
+                rate = (depth - 1) * G * nb * 8 * 1000 // 2500
                 rate = max(1, min(rate, 45 if shared else 30, 700 * min(tiles_m, wpx) // min(tiles, wpx)))
-                tile_ns = G * nb * kc // 32 * 1000 // rate + -(-kc // 256) * blocks * 100 + (3000 + 200 * KS if KS > 1 else 1000)
+                tile_ns = G * nb * kc // 32 * 1000 // rate + -(-kc // 256) * blocks * 100 + (3000 + 400 * KS if KS > 1 else 1000)
                 cost = -(-tiles // wpx) * tile_ns
                 if tiles % wpx:
                     cost += cost // 10      # idle or unequally loaded workers
