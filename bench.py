@@ -27,23 +27,23 @@ HBM_PEAK_GBPS = 8000.0
 # same counters read for a plain copy of known size.  Key: (batch, kv, kv_min, sched, tile_m, flags)
 # at 36 layers and seed 2; any other workload reports null unless --traffic-bytes is given.
 MEASURED_TRAFFIC = {
-    (1, 1024, 0, 0, 0, 0): 15444424640,
-    (1, 1024, 0, 1, 0, 0): 15430785120,
-    (1, 1024, 0, 0, 0, 64): 16208073664,
-    (1, 1024, 0, 0, 0, 256): 16263464000,
-    (8, 2048, 1024, 0, 0, 0): 17321967040,
-    (8, 2048, 1024, 0, 0, 4): 17341185344,
-    (8, 2048, 1024, 1, 0, 0): 17483146336,
-    (32, 2048, 1024, 0, 0, 0): 23732238272,
-    (32, 2048, 1024, 0, 16, 0): 24143764288,
-    (32, 2048, 1024, 1, 16, 0): 32709316352,
-    (32, 2048, 1024, 2, 16, 0): 38880241408,
-    (64, 4096, 0, 0, 0, 0): 55953641088,
-    (64, 4096, 0, 0, 16, 0): 57067202496,
-    (64, 4096, 0, 1, 16, 0): 81740070144,
-    (64, 4096, 0, 2, 16, 0): 100611870784,
-    (64, 4096, 0, 0, 16, 32): 56761924928,
-    (64, 4096, 0, 0, 16, 2048): 57060511104,
+    (1, 1024, 0, 0, 0, 0): 15442051776,
+    (1, 1024, 0, 1, 0, 0): 15429261600,
+    (1, 1024, 0, 0, 0, 64): 16206124928,
+    (1, 1024, 0, 0, 0, 256): 16262169472,
+    (8, 2048, 1024, 0, 0, 0): 17327702400,
+    (8, 2048, 1024, 0, 0, 4): 17340605696,
+    (8, 2048, 1024, 1, 0, 0): 17487098336,
+    (32, 2048, 1024, 0, 0, 0): 23603600192,
+    (32, 2048, 1024, 0, 16, 0): 24141093952,
+    (32, 2048, 1024, 1, 16, 0): 32711838336,
+    (32, 2048, 1024, 2, 16, 0): 38605158016,
+    (64, 4096, 0, 0, 0, 0): 55955680128,
+    (64, 4096, 0, 0, 16, 0): 57069072832,
+    (64, 4096, 0, 1, 16, 0): 81746746560,
+    (64, 4096, 0, 2, 16, 0): 100462085632,
+    (64, 4096, 0, 0, 16, 32): 56752676800,
+    (64, 4096, 0, 0, 16, 2048): 57058127808,
 }
 
 
