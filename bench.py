@@ -27,23 +27,23 @@ HBM_PEAK_GBPS = 8000.0
 # same counters read for a plain copy of known size.  Key: (batch, kv, kv_min, sched, tile_m, flags)
 # at 36 layers and seed 2; any other workload reports null unless --traffic-bytes is given.
 MEASURED_TRAFFIC = {
-    (1, 1024, 0, 0, 0, 0): 15442051776,
-    (1, 1024, 0, 1, 0, 0): 15429261600,
-    (1, 1024, 0, 0, 0, 64): 16206124928,
-    (1, 1024, 0, 0, 0, 256): 16262169472,
-    (8, 2048, 1024, 0, 0, 0): 17327702400,
-    (8, 2048, 1024, 0, 0, 4): 17340605696,
-    (8, 2048, 1024, 1, 0, 0): 17487098336,
-    (32, 2048, 1024, 0, 0, 0): 23603600192,
-    (32, 2048, 1024, 0, 16, 0): 24141093952,
-    (32, 2048, 1024, 1, 16, 0): 32711838336,
-    (32, 2048, 1024, 2, 16, 0): 38605158016,
-    (64, 4096, 0, 0, 0, 0): 55955680128,
-    (64, 4096, 0, 0, 16, 0): 57069072832,
-    (64, 4096, 0, 1, 16, 0): 81746746560,
-    (64, 4096, 0, 2, 16, 0): 100462085632,
-    (64, 4096, 0, 0, 16, 32): 56752676800,
-    (64, 4096, 0, 0, 16, 2048): 57058127808,
+    (1, 1024, 0, 0, 0, 0): 15450548864,
+    (1, 1024, 0, 1, 0, 0): 15431806304,
+    (1, 1024, 0, 0, 0, 64): 16205908416,
+    (1, 1024, 0, 0, 0, 256): 16262395008,
+    (8, 2048, 1024, 0, 0, 0): 17331194048,
+    (8, 2048, 1024, 0, 0, 4): 17343882048,
+    (8, 2048, 1024, 1, 0, 0): 17487087456,
+    (32, 2048, 1024, 0, 0, 0): 23608298240,
+    (32, 2048, 1024, 0, 16, 0): 24150736448,
+    (32, 2048, 1024, 1, 16, 0): 32720066496,
+    (32, 2048, 1024, 2, 16, 0): 38613665792,
+    (64, 4096, 0, 0, 0, 0): 55967937472,
+    (64, 4096, 0, 0, 16, 0): 57076790528,
+    (64, 4096, 0, 1, 16, 0): 81750251392,
+    (64, 4096, 0, 2, 16, 0): 100455350080,
+    (64, 4096, 0, 0, 16, 32): 56763077056,
+    (64, 4096, 0, 0, 16, 2048): 57070389632,
 }
 
 
